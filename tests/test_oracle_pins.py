@@ -1,0 +1,281 @@
+"""Pins for the oracle's round of Algorithm 1 (CoCoD-SGD), CPU only.
+
+The paper prints no worked example, so every pin is derived from its equations:
+special cases of Algorithm 1, the two model representations used in the proof of
+Lemma 2, a closed form for the noiseless quadratic, and a hand-computed case.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs
+from oracle import cocod_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+HYPER = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=77)
+
+
+def make(W, n, kind="f64", data_seed=3, **kw):
+    h, c = synth_inputs.quadratic_data(data_seed, W, n)
+    return orc.QuadraticOracle(h, c, kind=kind, **kw)
+
+
+def plain_sgd(h, c, steps, *, lr, momentum=0.0, weight_decay=0.0, noise_sigma=0.0, seed=0, worker=0):
+    """Textbook momentum SGD on one worker in numpy fp64 (not the oracle's step loop)."""
+    lr, mu, wd, sg = (orc.f32(t) for t in (lr, momentum, weight_decay, noise_sigma))
+    h = h.astype(np.float64)
+    c = c.astype(np.float64)
+    x = np.zeros_like(h)
+    v = np.zeros_like(h)
+    for s in range(steps):
+        z = orc.normals(seed, orc.TAG_NOISE, worker, s, 0, h.size) if sg else 0.0
+        g = h * (x - c) + sg * z + wd * x
+        v = mu * v + g
+        x = x - lr * v
+    return x
+
+
+# ---- hand-computed case (tests/golden/hand_case_W2_d1.txt) -------------------------------
+
+def test_hand_case():
+    h = np.array([[1.0], [2.0]], np.float32)
+    c = np.array([[1.0], [-1.0]], np.float32)
+    rows = []
+    with open(os.path.join(GOLDEN, "hand_case_W2_d1.txt")) as fh:
+        for line in fh:
+            if not line.startswith("#") and line.strip():
+                rows.append(line.split())
+    assert len(rows) == 5
+    for mu in (0.0, 0.5):
+        # lr 0.1 is not an fp32 number; the hand arithmetic is in exact decimals
+        o = orc.QuadraticOracle(h, c, lr=0.1, momentum=mu)
+        o.lr = 0.1
+        for row in [r for r in rows if float(r[0]) == mu]:
+            o.round(2)
+            assert o.step == 2 * int(row[1])
+            assert np.allclose(o.x[:, 0], [float(row[2]), float(row[3])], rtol=0, atol=1e-14)
+            if mu:
+                assert np.allclose(o.v[:, 0], [float(row[4]), float(row[5])], rtol=0, atol=1e-13)
+
+
+# ---- special cases of Algorithm 1 --------------------------------------------------------
+
+def test_single_worker_is_plain_sgd():
+    """N = 1: the mean is the stored model, so line 6 returns the local model."""
+    n, R, k = 257, 6, 3
+    o = make(1, n, **HYPER)
+    for r in range(R):
+        o.round(k)
+        if r == 0:                       # x0 = 0: snapshot and mean are 0, line 6 is exact
+            first = plain_sgd(o.h[0], o.c[0], k, **HYPER)
+            assert np.array_equal(o.x[0], first)
+    want = plain_sgd(o.h[0], o.c[0], R * k, **HYPER)
+    assert np.max(np.abs(o.x[0] - want)) < 1e-14
+
+
+def test_single_worker_with_nonzero_start_and_split_calls():
+    n = 64
+    h, c = synth_inputs.quadratic_data(5, 1, n)
+    x0 = np.linspace(-1, 1, n)
+    a = orc.QuadraticOracle(h, c, x0, **HYPER)
+    b = orc.QuadraticOracle(h, c, x0, **HYPER)
+    a.round(4)
+    b.average_begin(); b.local_steps(1); b.local_steps(3); b.average_end_apply()
+    assert np.array_equal(a.x, b.x) and np.array_equal(a.v, b.v) and a.step == b.step == 4
+
+
+@pytest.mark.parametrize("W", [4, 16])
+def test_identical_workers_without_noise_follow_one_worker(W):
+    n, R, k = 100, 5, 2
+    h1, c1 = synth_inputs.quadratic_data(8, 1, n)
+    hyper = dict(HYPER, noise_sigma=0.0)
+    o = orc.QuadraticOracle(np.repeat(h1, W, 0), np.repeat(c1, W, 0), **hyper)
+    for _ in range(R):
+        o.round(k)
+    for i in range(1, W):
+        assert np.array_equal(o.x[i], o.x[0])
+    want = plain_sgd(h1[0], c1[0], R * k, **hyper)
+    assert np.max(np.abs(o.x[0] - want)) < 1e-14
+
+
+def test_zero_local_steps_gives_pure_averaging():
+    o = make(4, 33, **HYPER)
+    o.local_steps(3)                      # make the workers disagree first
+    mean_before = o.x.mean(axis=0)
+    o.average_begin(); o.average_end_apply()
+    for i in range(4):
+        assert np.allclose(o.x[i], mean_before, rtol=0, atol=1e-15)
+
+
+def test_first_round_correction_is_identity():
+    """All workers start from the same point, so the first mean equals it (initialisation of Algorithm 1)."""
+    W, n, k = 4, 50, 3
+    o = make(W, n, **HYPER)
+    ref = make(W, n, **HYPER)
+    o.round(k)
+    ref.local_steps(k)
+    assert np.array_equal(o.x, ref.x)
+
+
+# ---- representations from the proof of Lemma 2 -------------------------------------------
+
+def test_correction_preserves_worker_mean_and_resets_deviation():
+    """After line 6: mean_i x_i = mean + mean_i delta_i, and x_i - mean_i x_i = delta_i - mean delta."""
+    W, n, k = 8, 40, 3
+    o = make(W, n, **HYPER)
+    o.round(2); o.round(2)                 # get a state where workers differ
+    o.average_begin()
+    snap, mean = o.snap.copy(), o.mean.copy()
+    assert np.allclose(mean, snap.mean(axis=0), rtol=0, atol=1e-15)
+    o.local_steps(k)
+    pre = o.x.copy()
+    o.average_end_apply()
+    delta = pre - snap
+    assert np.allclose(o.x.mean(axis=0), mean + delta.mean(axis=0), rtol=0, atol=1e-14)
+    assert np.allclose(o.x.mean(axis=0), pre.mean(axis=0), rtol=0, atol=1e-14)
+    assert np.allclose(o.x - o.x.mean(axis=0), delta - delta.mean(axis=0), rtol=0, atol=1e-14)
+
+
+def test_local_model_is_mean_minus_summed_gradients():
+    """Plain SGD (no momentum, no weight decay): x_i after line 6 = mean_t - lr * sum of G over the round."""
+    W, n, k = 4, 30, 4
+    hyper = dict(lr=0.1, noise_sigma=0.01, seed=9)
+    o = make(W, n, **hyper)
+    o.round(k)
+    o.average_begin()
+    mean = o.mean.copy()
+    grads = o.local_steps(k, log_gradients=True)
+    o.average_end_apply()
+    want = mean[None, :] - o.lr * np.sum(grads, axis=0)
+    assert np.max(np.abs(o.x - want)) < 1e-14
+    # and the averaged model moves by the averaged gradients
+    assert np.allclose(o.x.mean(axis=0), mean - o.lr * np.sum(grads, axis=0).mean(axis=0), rtol=0, atol=1e-14)
+
+
+def test_weighted_mean_invariant():
+    W, n, k = 4, 20, 2
+    p = np.array([1, 2, 2, 3], np.float64) / 8
+    h, c = synth_inputs.quadratic_data(21, W, n)
+    o = orc.QuadraticOracle(h, c, weights=p, **HYPER)
+    o.round(k)
+    o.average_begin()
+    assert np.allclose(o.mean, p @ o.snap, rtol=0, atol=1e-15)
+    o.local_steps(k)
+    pre = o.x.copy()
+    o.average_end_apply()
+    assert np.allclose(p @ o.x, p @ pre, rtol=0, atol=1e-14)
+    # equal weights are the uniform mean
+    a = orc.QuadraticOracle(h, c, weights=np.full(W, 0.25), **HYPER)
+    b = orc.QuadraticOracle(h, c, **HYPER)
+    a.round(k); a.round(k); b.round(k); b.round(k)
+    assert np.array_equal(a.x, b.x)
+
+
+def test_shared_curvature_mean_follows_mean_objective():
+    """Same h on every worker, no noise: the averaged model is single-worker SGD on the averaged centre."""
+    W, n, R, k = 4, 60, 5, 3
+    h1, _ = synth_inputs.quadratic_data(1, 1, n)
+    _, c = synth_inputs.quadratic_data(2, W, n)
+    hyper = dict(HYPER, noise_sigma=0.0)
+    o = orc.QuadraticOracle(np.repeat(h1, W, 0), c, **hyper)
+    for _ in range(R):
+        o.round(k)
+    lr, mu, wd = (orc.f32(hyper[t]) for t in ("lr", "momentum", "weight_decay"))
+    hh = h1[0].astype(np.float64)
+    cbar = c.astype(np.float64).mean(axis=0)
+    x = np.zeros(n); v = np.zeros(n)
+    for _ in range(R * k):
+        v = mu * v + hh * (x - cbar) + wd * x
+        x = x - lr * v
+    assert np.max(np.abs(o.x.mean(axis=0) - x)) < 1e-13
+
+
+# ---- closed form: the round is an affine map per coordinate -------------------------------
+
+def round_matrix(h, c, lr, mu, wd, k):
+    """(2W+1)x(2W+1) homogeneous matrix of one round acting on (x_1..x_W, v_1..v_W, 1)."""
+    W = h.size
+    L = np.eye(2 * W + 1)
+    for i in range(W):
+        a, b = h[i] + wd, h[i] * c[i]
+        # v' = mu v + a x - b ;  x' = x - lr v'
+        L[W + i, W + i] = mu; L[W + i, i] = a; L[W + i, -1] = -b
+        L[i, i] = 1 - lr * a; L[i, W + i] = -lr * mu; L[i, -1] = lr * b
+    M = np.linalg.matrix_power(L, k)
+    M[:W, :W] += np.full((W, W), 1.0 / W) - np.eye(W)      # + (mean - own) of the stored models
+    return M
+
+
+@pytest.mark.parametrize("mu,wd,k", [(0.0, 0.0, 4), (0.9, 5e-4, 2), (0.5, 0.01, 1)])
+def test_noiseless_trajectory_matches_affine_closed_form(mu, wd, k):
+    W, n, R = 4, 12, 10
+    h, c = synth_inputs.quadratic_data(31, W, n)
+    o = orc.QuadraticOracle(h, c, lr=0.1, momentum=mu, weight_decay=wd)
+    for _ in range(R):
+        o.round(k)
+    for j in range(n):
+        M = round_matrix(h[:, j].astype(np.float64), c[:, j].astype(np.float64),
+                         orc.f32(0.1), orc.f32(mu), orc.f32(wd), k)
+        state = np.zeros(2 * W + 1); state[-1] = 1.0
+        state = np.linalg.matrix_power(M, R) @ state
+        assert np.max(np.abs(o.x[:, j] - state[:W])) < 1e-12
+        if mu:
+            assert np.max(np.abs(o.v[:, j] - state[W:2 * W])) < 1e-11
+
+
+def test_plain_sgd_closed_form_scalar():
+    """mu = 0: x after a round is (J + D) x - D c with D = diag((1 - lr h)^k - 1), J = averaging."""
+    W, k, R, lr = 3, 4, 7, orc.f32(0.1)
+    h = np.array([[0.5], [1.0], [2.0]], np.float32)
+    c = np.array([[1.0], [-2.0], [0.25]], np.float32)
+    o = orc.QuadraticOracle(h, c, lr=0.1)
+    x = np.zeros(W)
+    D = np.diag((1 - lr * h[:, 0].astype(np.float64)) ** k - 1)
+    J = np.full((W, W), 1 / W)
+    for _ in range(R):
+        o.round(k)
+        x = (J + D) @ x - D @ c[:, 0].astype(np.float64)
+        assert np.max(np.abs(o.x[:, 0] - x)) < 1e-13
+
+
+# ---- structure -----------------------------------------------------------------------------
+
+def test_subset_equals_full_run():
+    """The synthetic objective is separable: any column subset reproduces the full run bit for bit."""
+    W, n, R, k = 4, 1000, 3, 2
+    h, c = synth_inputs.quadratic_data(17, W, n)
+    full = orc.QuadraticOracle(h, c, **HYPER)
+    idx = np.array([0, 1, 2, 3, 4, 7, 8, 250, 251, 997, 998, 999], np.uint64)
+    ii = idx.astype(np.int64)
+    sub = orc.QuadraticOracle(h[:, ii], c[:, ii], idx=idx, **HYPER)
+    for _ in range(R):
+        full.round(k); sub.round(k)
+    assert np.array_equal(sub.x, full.x[:, ii]) and np.array_equal(sub.v, full.v[:, ii])
+
+
+def test_f32_mirror_stays_close_to_reference():
+    """The fp32 mirror drifts from fp64 far less than the 1e-5 parity budget on the tiny config."""
+    cfg = synth_inputs.CONFIGS["C1_tiny"]
+    W, n = cfg["W"], 4096
+    h, c = synth_inputs.quadratic_data(cfg["seed"], W, n)
+    kw = dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"],
+              noise_sigma=cfg["noise_sigma"], seed=cfg["seed"])
+    a = orc.QuadraticOracle(h, c, kind="f64", **kw)
+    b = orc.QuadraticOracle(h, c, kind="f32", **kw)
+    for _ in range(cfg["rounds"]):
+        a.round(cfg["k"][0]); b.round(cfg["k"][0])
+    assert np.max(np.abs(a.x - b.x) / (1 + np.abs(a.x))) < 2e-6
+
+
+def test_step_counter_is_global_across_rounds():
+    """Noise is keyed by the global step t, which continues across rounds (tau = t .. t+k-1)."""
+    W, n = 2, 16
+    h = np.zeros((W, n), np.float32); c = np.zeros((W, n), np.float32)
+    o = orc.QuadraticOracle(h, c, lr=1.0, noise_sigma=1.0, seed=4)
+    o.round(2)
+    assert o.step == 2
+    before = o.x.copy()
+    o.average_begin(); o.local_steps(1)
+    z = np.stack([orc.normals(4, orc.TAG_NOISE, i, 2, 0, n) for i in range(W)])
+    assert np.allclose(o.x, before - z, rtol=0, atol=1e-15)
