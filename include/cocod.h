@@ -1,0 +1,210 @@
+/*
+ * libcocod -- one round of CoCoD-SGD (computation and communication decoupled
+ * SGD) for W simulated workers resident in one GPU's memory.
+ *
+ * The round is the body of the while loop of Algorithm 1 of the paper:
+ *   Step I   store every worker's model x_t^i and form the weighted mean of the
+ *            stored models, x^_t = sum_i p_i x_t^i           (cocod_average_begin)
+ *   Step II  k local stochastic-gradient steps on the live model, concurrently
+ *            with Step I                                     (cocod_local_steps)
+ *   line 6   x_{t+k}^i = x^_t + (x_{t+k}^i - x_t^i)         (cocod_average_end_apply)
+ *   line 7   t = t + k                                       (the step counter)
+ * The paper's all-reduce between workers is, on one GPU, a reduction over the
+ * worker axis on a second stream that overlaps the local steps.
+ *
+ * Conventions
+ *   - plain C ABI; every function returns a cocod_status (0 = ok, < 0 = error)
+ *     unless stated otherwise; no exception crosses the boundary.
+ *   - "device" pointers are HIP device memory, "host" pointers ordinary memory.
+ *   - every call only ENQUEUES work on the caller's streams; nothing waits for
+ *     the GPU except cocod_create (with COCOD_FLAG_SELFTEST never), cocod_sync
+ *     and cocod_destroy.
+ *   - the caller owns all large device buffers and both streams; they must
+ *     outlive the context.  The context owns its chunk table, two events, the
+ *     optional weight vector and the MLP work space.
+ *   - argument errors are detected before any GPU call is made.
+ *   - a context is not thread safe; use it from one host thread at a time.
+ */
+#ifndef COCOD_H
+#define COCOD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cocod_ctx cocod_ctx;
+
+typedef enum cocod_status {
+    COCOD_OK = 0,
+    COCOD_ERR_INVALID = -1,      /* bad argument (null, misaligned, out of range, inconsistent) */
+    COCOD_ERR_STATE = -2,        /* call not legal in the current state of the round */
+    COCOD_ERR_HIP = -3,          /* a HIP runtime call failed; see cocod_last_error */
+    COCOD_ERR_NOMEM = -4,        /* host or device allocation failed */
+    COCOD_ERR_UNSUPPORTED = -5   /* valid request this build does not implement */
+} cocod_status;
+
+/* Where the stochastic gradient G of Step II comes from. */
+typedef enum cocod_grad_kind {
+    /* G_j = h_ij (x_j - c_ij) + sigma z(seed, i, t, j): separable quadratic with seeded noise
+       standing in for the mini-batch gradient of Step II. */
+    COCOD_GRAD_QUADRATIC = 0,
+    /* G = gradient of the mean softmax cross-entropy of a two-layer ReLU perceptron on a fresh
+       seeded mini-batch per (worker, step): a real mini-batch gradient, dense contractions. */
+    COCOD_GRAD_MLP = 1
+} cocod_grad_kind;
+
+/* How Step I is scheduled relative to Step II (the arithmetic is the same in all three). */
+typedef enum cocod_schedule {
+    COCOD_SCHED_OVERLAP = 0,   /* mean on avg_stream, concurrent with the local steps (the paper's scheme) */
+    COCOD_SCHED_SERIAL = 1,    /* mean on compute_stream after the local steps, then line 6 (sequential, as
+                                  the paper's Local-SGD timeline) */
+    COCOD_SCHED_FUSED = 2      /* mean and line 6 in one kernel after the local steps */
+} cocod_schedule;
+
+enum {
+    COCOD_FLAG_DRY_RUN = 1u    /* validate, plan and track state but make no GPU call at all (host tests) */
+};
+
+/*
+ * Memory layout.  Every per-worker array is worker-major: element e of worker i
+ * lives at base[i * stride + e], 0 <= e < padded_d.  A flat model (n_tensors <= 1)
+ * has padded_d = d rounded up to 4.  A parameter list of n_tensors tensors is
+ * packed in list order, each tensor starting on a 16-byte boundary (offset
+ * multiple of 4 elements); see cocod_plan_layout.  Pad elements are carried
+ * along by the averaging kernels and never influence real elements.
+ */
+typedef struct cocod_config {
+    uint32_t struct_size;          /* sizeof(cocod_config); checked */
+    uint32_t W;                    /* number of workers N of Algorithm 1, >= 1 */
+    uint64_t d;                    /* parameters per worker (sum of tensor sizes), >= 1, < 2^34 */
+    uint32_t n_tensors;            /* 0 or 1: one flat vector; else length of tensor_numel */
+    uint32_t grad;                 /* cocod_grad_kind */
+    const uint64_t *tensor_numel;  /* host, [n_tensors], each >= 1, sum == d; copied */
+    uint64_t bucket_bytes;         /* averaging granularity: tensors are grouped, in order, into buckets of
+                                      at most this many bytes (a larger tensor gets its own); 0 = one bucket */
+    float lr;                      /* gamma */
+    float momentum;                /* mu of the experiments' optimizer; 0 = the update of Algorithm 1 */
+    float weight_decay;            /* lambda, added to the gradient as lambda x */
+    float noise_sigma;             /* sigma of the gradient noise (quadratic kind) */
+    uint64_t seed;                 /* key of the counter-based generator */
+    const float *weights;          /* host, [W], p_i = M_i / sum M_l, must sum to 1 within 1e-4; NULL = 1/W */
+    float *xA;                     /* device [W][stride]: holds the models at create time (the live buffer) */
+    float *xB;                     /* device [W][stride]: second model buffer; need not be initialised */
+    float *v;                      /* device [W][stride]: momentum buffer, caller-initialised (0 for a fresh
+                                      run); may be NULL when momentum == 0 */
+    float *mean;                   /* device [stride]: receives x^_t */
+    const float *h;                /* device [W][stride]: curvatures (quadratic kind) */
+    const float *c;                /* device [W][stride]: centres (quadratic kind) */
+    uint64_t stride;               /* elements between consecutive workers; >= padded_d, multiple of 4 */
+    void *compute_stream;          /* hipStream_t for Step II and line 6 (NULL = the null stream) */
+    void *avg_stream;              /* hipStream_t for Step I; equal to compute_stream = no overlap */
+    uint32_t mlp_in, mlp_hidden, mlp_out, mlp_batch;   /* MLP kind: layer widths and mini-batch size */
+    uint32_t flags;                /* COCOD_FLAG_* */
+} cocod_config;
+
+/*
+ * Plan the packed layout of a parameter list (pure host arithmetic, no GPU).
+ *   d, n_tensors, tensor_numel, bucket_bytes: as in cocod_config.
+ *   padded_d      out: elements per worker including alignment pads.
+ *   tensor_offset out, may be NULL: [n_tensors] element offset of each tensor inside a worker.
+ *   n_buckets     out, may be NULL.
+ *   bucket_begin  out, may be NULL: [n_tensors + 1] capacity; bucket b covers elements
+ *                 [bucket_begin[b], bucket_begin[b+1]) of a worker; n_buckets + 1 entries written.
+ * Follows the packed-buffer practice of the communication library the paper used
+ * (tensor fusion); the paper itself only needs "the model" as one vector.
+ */
+int cocod_plan_layout(uint64_t d, uint32_t n_tensors, const uint64_t *tensor_numel,
+                      uint64_t bucket_bytes, uint64_t *padded_d, uint64_t *tensor_offset,
+                      uint32_t *n_buckets, uint64_t *bucket_begin);
+
+/*
+ * Initialisation of Algorithm 1: validates cfg, plans the layout, builds the
+ * device chunk table and creates the events.  xA must already hold x_0^i for
+ * every worker (the paper starts all workers from the same point; the library
+ * does not require it).  On success *out receives the context (state IDLE,
+ * step counter t = 0, live buffer xA).  On failure *out is NULL and
+ * cocod_last_error(NULL) describes the reason.
+ */
+int cocod_create(const cocod_config *cfg, cocod_ctx **out);
+
+/* Waits for both streams, frees what the context owns.  NULL is accepted. */
+int cocod_destroy(cocod_ctx *ctx);
+
+/*
+ * Step II: enqueue k >= 0 local steps on compute_stream.  Each step computes the
+ * stochastic gradient G_t^i at the live model and applies
+ *     g = G + lambda x ;  v = mu v + g ;  x = x - gamma v          (mu = 0: x = x - gamma g)
+ * and advances the step counter t by one.  Legal in both states; outside a round
+ * it is plain local SGD.  The first step after cocod_average_begin reads the
+ * stored model and writes the other model buffer, so storing x_t^i costs no copy.
+ */
+int cocod_local_steps(cocod_ctx *ctx, int k);
+
+/*
+ * Step I: marks the live models as the stored models x_t^i and (OVERLAP schedule)
+ * enqueues the weighted mean on avg_stream, ordered after all work already on
+ * compute_stream.  IDLE -> AVERAGING; COCOD_ERR_STATE if already averaging.
+ */
+int cocod_average_begin(cocod_ctx *ctx);
+
+/*
+ * Join and line 6: compute_stream waits for the mean and then applies
+ * x^i = x^_t + (x^i - x_t^i) to every worker (with zero local steps since begin this
+ * leaves every worker at x^_t).  AVERAGING -> IDLE; COCOD_ERR_STATE if not averaging.
+ */
+int cocod_average_end_apply(cocod_ctx *ctx);
+
+/* Choose how Step I is scheduled; only legal while IDLE.  Default COCOD_SCHED_OVERLAP. */
+int cocod_set_schedule(cocod_ctx *ctx, int schedule);
+
+/* Learning-rate schedules live in the caller: set gamma between steps. */
+int cocod_set_lr(cocod_ctx *ctx, float lr);
+
+/* The global step counter t (line 7).  It keys the noise / mini-batch streams, so a run that is
+   saved (models, momentum, t) and restored continues bit-identically.  t < 2^32. */
+int cocod_get_step(const cocod_ctx *ctx, uint64_t *step);
+int cocod_set_step(cocod_ctx *ctx, uint64_t step);
+
+/* Which of xA / xB currently holds the models (device pointer, [W][stride]). */
+int cocod_live_model(const cocod_ctx *ctx, float **x_live);
+
+/* 1 while a round is open (between begin and end_apply), else 0; < 0 on error. */
+int cocod_is_averaging(const cocod_ctx *ctx);
+
+/* Number of chunks of the step kernel's chunk table and number of buckets (for inspection). */
+int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks, uint32_t *n_buckets);
+
+/* Block the host until both streams have drained. */
+int cocod_sync(cocod_ctx *ctx);
+
+/*
+ * Draw the synthetic objective on the device (quadratic kind): fills the buffers
+ * behind cfg.h and cfg.c on compute_stream with h_ij = 0.5 + 1.5 U and c_ij ~ N(0,1)
+ * from the counter-based generator (streams 1 and 2 of the seed), pads set to 0.
+ * For models too large to generate on the host.
+ */
+int cocod_fill_quadratic(cocod_ctx *ctx);
+
+/*
+ * Generator check: n standard normals of stream `tag` for (worker, step) at flat
+ * indices j0 .. j0+n-1, written to device memory `out` on `stream`, produced by the
+ * same device routine as the local step's noise (fast = 1) or by the accurate routine
+ * used for the objective data (fast = 0).  No context needed.
+ */
+int cocod_debug_normals(void *stream, uint64_t seed, uint32_t tag, uint32_t worker, uint32_t step,
+                        uint64_t j0, uint64_t n, int fast, float *out);
+
+/* Last error text of ctx, or of the last failed cocod_create / context-free call when ctx is NULL.
+   Never NULL; owned by the library; valid until the next call on the same context / thread. */
+const char *cocod_last_error(const cocod_ctx *ctx);
+
+/* Library version, major * 1000 + minor. */
+int cocod_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COCOD_H */

@@ -254,3 +254,11 @@ void oracle_round(int W, size_t n, const uint64_t *idx, REAL *x, REAL *v, REAL *
 }
 
 int oracle_real_bytes(void) { return (int)sizeof(REAL); }
+
+/* number of threads the parallel loops above use (for reporting the CPU baseline) */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

@@ -40,6 +40,7 @@ def _lib(kind):
                      "oracle_mean", "oracle_correct", "oracle_round"):
             getattr(lib, name).restype = None
         lib.oracle_real_bytes.restype = C.c_int
+        lib.oracle_num_threads.restype = C.c_int
         _libs[kind] = lib
     return _libs[kind]
 
@@ -83,6 +84,10 @@ def fill_quadratic(seed, W, n=None, idx=None):
     c = np.zeros((W, n), dtype=np.float32)
     _lib("f64").oracle_fill_quadratic(seed, W, n, _p(idx), _p(h), _p(c))
     return h, c
+
+
+def num_threads():
+    return _lib("f64").oracle_num_threads()
 
 
 def f32(value):

@@ -1,0 +1,455 @@
+// Host side of libcocod: argument validation, layout planning, the state machine of
+// one CoCoD-SGD round (Algorithm 1: Step I and Step II in parallel, then line 6)
+// and the stream/event choreography that makes the two steps overlap on one GPU.
+// No arithmetic on model data happens here; every step of the round is a kernel.
+#include "../../include/cocod.h"
+#include "internal.hpp"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using cocod::Chunk;
+
+struct cocod_ctx {
+    cocod_config cfg{};                 // copy of the caller's config (host array pointers cleared)
+    std::vector<uint64_t> tensor_numel, tensor_offset, bucket_begin;
+    uint64_t padded_d = 0;
+    std::vector<Chunk> chunks;
+    Chunk *d_chunks = nullptr;          // device copy of the chunk table (owned)
+    float *d_weights = nullptr;         // device copy of p_i (owned), nullptr = uniform
+    hipEvent_t ev_snap = nullptr;       // compute stream reached the point where the models are stored
+    hipEvent_t ev_mean = nullptr;       // mean of the stored models is complete
+    hipStream_t s_compute = nullptr, s_avg = nullptr;
+    float *live = nullptr;              // buffer holding the current models
+    float *spare = nullptr;             // the other model buffer
+    const float *snap = nullptr;        // stored models x_t^i of the open round (aliases one of the two)
+    bool averaging = false;             // a round is open
+    bool store_pending = false;         // next local step must write out of place (keeps the stored models intact)
+    int schedule = COCOD_SCHED_OVERLAP;
+    uint64_t step = 0;                  // global step counter t
+    bool dry = false;
+    std::string err;
+};
+
+namespace {
+
+thread_local std::string g_err;         // errors that have no context to live in
+
+int fail(cocod_ctx *ctx, int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_err = buf;
+    return code;
+}
+
+int hip_fail(cocod_ctx *ctx, hipError_t e, const char *what)
+{
+    return fail(ctx, COCOD_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define COCOD_HIP(ctx, call)                                             \
+    do {                                                                 \
+        hipError_t e_ = (call);                                          \
+        if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);         \
+    } while (0)
+
+inline uint64_t round_up4(uint64_t n) { return (n + 3u) & ~static_cast<uint64_t>(3u); }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Layout of a parameter list: tensors in order, each start rounded up to 4 elements;
+// buckets are maximal runs of tensors whose padded extent fits bucket_bytes.
+int plan(uint64_t d, uint32_t n_tensors, const uint64_t *numel, uint64_t bucket_bytes,
+         std::vector<uint64_t> &sizes, std::vector<uint64_t> &offsets, std::vector<uint64_t> &bucket_begin,
+         uint64_t &padded_d)
+{
+    if (d == 0) return fail(nullptr, COCOD_ERR_INVALID, "d must be >= 1");
+    if (d >= (1ull << 34)) return fail(nullptr, COCOD_ERR_INVALID, "d must be < 2^34 (generator counter width)");
+    sizes.clear(); offsets.clear(); bucket_begin.clear();
+    if (n_tensors <= 1) {
+        if (n_tensors == 1 && numel && numel[0] != d)
+            return fail(nullptr, COCOD_ERR_INVALID, "tensor_numel[0] != d");
+        sizes.push_back(d);
+    } else {
+        if (!numel) return fail(nullptr, COCOD_ERR_INVALID, "tensor_numel is NULL with n_tensors > 1");
+        uint64_t sum = 0;
+        for (uint32_t t = 0; t < n_tensors; ++t) {
+            if (numel[t] == 0) return fail(nullptr, COCOD_ERR_INVALID, "tensor %u is empty", t);
+            if (numel[t] > d) return fail(nullptr, COCOD_ERR_INVALID, "tensor %u larger than d", t);
+            sum += numel[t];
+            sizes.push_back(numel[t]);
+        }
+        if (sum != d) return fail(nullptr, COCOD_ERR_INVALID, "tensor sizes sum to %llu, d is %llu",
+                                  (unsigned long long)sum, (unsigned long long)d);
+    }
+    uint64_t at = 0;
+    for (uint64_t n : sizes) { offsets.push_back(at); at = round_up4(at + n); }
+    padded_d = at;
+    const uint64_t cap = bucket_bytes / sizeof(float);
+    bucket_begin.push_back(0);
+    uint64_t bucket_start = 0;
+    for (size_t t = 1; t < sizes.size(); ++t) {
+        const uint64_t end_with_t = round_up4(offsets[t] + sizes[t]);
+        if (cap != 0 && end_with_t - bucket_start > cap) {   // tensor t does not fit: it opens a new bucket
+            bucket_begin.push_back(offsets[t]);
+            bucket_start = offsets[t];
+        }
+    }
+    bucket_begin.push_back(padded_d);
+    return COCOD_OK;
+}
+
+bool overlap(const void *a, uint64_t a_bytes, const void *b, uint64_t b_bytes)
+{
+    if (!a || !b) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+int validate(const cocod_config *cfg, uint64_t padded_d)
+{
+    const unsigned known_flags = COCOD_FLAG_DRY_RUN;
+    if (cfg->flags & ~known_flags) return fail(nullptr, COCOD_ERR_INVALID, "unknown flag bits 0x%x", cfg->flags & ~known_flags);
+    if (cfg->W == 0 || cfg->W > 65535u) return fail(nullptr, COCOD_ERR_INVALID, "W must be in 1..65535");
+    if (cfg->grad != COCOD_GRAD_QUADRATIC && cfg->grad != COCOD_GRAD_MLP)
+        return fail(nullptr, COCOD_ERR_INVALID, "unknown gradient kind %u", cfg->grad);
+    if (cfg->stride < padded_d || (cfg->stride & 3u))
+        return fail(nullptr, COCOD_ERR_INVALID, "stride %llu must be a multiple of 4 and >= padded size %llu",
+                    (unsigned long long)cfg->stride, (unsigned long long)padded_d);
+    if (!std::isfinite(cfg->lr)) return fail(nullptr, COCOD_ERR_INVALID, "lr is not finite");
+    if (!(cfg->momentum >= 0.0f && cfg->momentum < 1.0f)) return fail(nullptr, COCOD_ERR_INVALID, "momentum must be in [0,1)");
+    if (!(cfg->weight_decay >= 0.0f) || !std::isfinite(cfg->weight_decay)) return fail(nullptr, COCOD_ERR_INVALID, "weight_decay must be finite and >= 0");
+    if (!(cfg->noise_sigma >= 0.0f) || !std::isfinite(cfg->noise_sigma)) return fail(nullptr, COCOD_ERR_INVALID, "noise_sigma must be finite and >= 0");
+    if (!cfg->xA || !cfg->xB || !cfg->mean) return fail(nullptr, COCOD_ERR_INVALID, "xA, xB and mean must not be NULL");
+    if (cfg->momentum != 0.0f && !cfg->v) return fail(nullptr, COCOD_ERR_INVALID, "v must not be NULL when momentum != 0");
+    if (cfg->grad == COCOD_GRAD_QUADRATIC && (!cfg->h || !cfg->c))
+        return fail(nullptr, COCOD_ERR_INVALID, "h and c must not be NULL for the quadratic gradient");
+    const void *ptrs[] = { cfg->xA, cfg->xB, cfg->v, cfg->mean, cfg->h, cfg->c };
+    const char *names[] = { "xA", "xB", "v", "mean", "h", "c" };
+    for (int i = 0; i < 6; ++i)
+        if (!aligned16(ptrs[i])) return fail(nullptr, COCOD_ERR_INVALID, "%s is not 16-byte aligned", names[i]);
+    const uint64_t big = static_cast<uint64_t>(cfg->W) * cfg->stride * sizeof(float);
+    const uint64_t sizes[] = { big, big, big, cfg->stride * sizeof(float), big, big };
+    for (int i = 0; i < 6; ++i)
+        for (int j = i + 1; j < 6; ++j)
+            if (overlap(ptrs[i], sizes[i], ptrs[j], sizes[j]))
+                return fail(nullptr, COCOD_ERR_INVALID, "%s and %s overlap", names[i], names[j]);
+    if (cfg->weights) {
+        double sum = 0.0;
+        for (uint32_t i = 0; i < cfg->W; ++i) {
+            if (!(cfg->weights[i] >= 0.0f) || !std::isfinite(cfg->weights[i]))
+                return fail(nullptr, COCOD_ERR_INVALID, "weights[%u] must be finite and >= 0", i);
+            sum += cfg->weights[i];
+        }
+        if (std::fabs(sum - 1.0) > 1e-4) return fail(nullptr, COCOD_ERR_INVALID, "weights sum to %g, not 1", sum);
+    }
+    if (cfg->grad == COCOD_GRAD_MLP)
+        return fail(nullptr, COCOD_ERR_UNSUPPORTED, "the MLP gradient is not built into this library version");
+    return COCOD_OK;
+}
+
+void release(cocod_ctx *ctx)
+{
+    if (!ctx->dry) {
+        if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
+        if (ctx->d_weights) (void)hipFree(ctx->d_weights);
+        if (ctx->ev_snap) (void)hipEventDestroy(ctx->ev_snap);
+        if (ctx->ev_mean) (void)hipEventDestroy(ctx->ev_mean);
+    }
+    delete ctx;
+}
+
+// Step I arithmetic on `stream`, one launch per bucket.
+int enqueue_mean(cocod_ctx *ctx, hipStream_t stream)
+{
+    for (size_t b = 0; b + 1 < ctx->bucket_begin.size(); ++b)
+        COCOD_HIP(ctx, cocod::launch_wmean(stream, ctx->snap, ctx->cfg.stride, ctx->cfg.W, ctx->bucket_begin[b],
+                                           ctx->bucket_begin[b + 1], ctx->d_weights, ctx->cfg.mean));
+    return COCOD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cocod_version(void) { return 1000; }
+
+const char *cocod_last_error(const cocod_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+int cocod_plan_layout(uint64_t d, uint32_t n_tensors, const uint64_t *tensor_numel, uint64_t bucket_bytes,
+                      uint64_t *padded_d, uint64_t *tensor_offset, uint32_t *n_buckets, uint64_t *bucket_begin)
+{
+    if (!padded_d) return fail(nullptr, COCOD_ERR_INVALID, "padded_d is NULL");
+    std::vector<uint64_t> sizes, offsets, buckets;
+    uint64_t pd = 0;
+    const int rc = plan(d, n_tensors, tensor_numel, bucket_bytes, sizes, offsets, buckets, pd);
+    if (rc != COCOD_OK) return rc;
+    *padded_d = pd;
+    if (tensor_offset) std::memcpy(tensor_offset, offsets.data(), offsets.size() * sizeof(uint64_t));
+    if (n_buckets) *n_buckets = static_cast<uint32_t>(buckets.size() - 1);
+    if (bucket_begin) std::memcpy(bucket_begin, buckets.data(), buckets.size() * sizeof(uint64_t));
+    return COCOD_OK;
+}
+
+int cocod_create(const cocod_config *cfg, cocod_ctx **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return fail(nullptr, COCOD_ERR_INVALID, "cfg and out must not be NULL");
+    if (cfg->struct_size != sizeof(cocod_config))
+        return fail(nullptr, COCOD_ERR_INVALID, "struct_size %u does not match this library (%zu)", cfg->struct_size,
+                    sizeof(cocod_config));
+    cocod_ctx *ctx = new (std::nothrow) cocod_ctx;
+    if (!ctx) return fail(nullptr, COCOD_ERR_NOMEM, "out of host memory");
+    int rc = plan(cfg->d, cfg->n_tensors, cfg->tensor_numel, cfg->bucket_bytes, ctx->tensor_numel, ctx->tensor_offset,
+                  ctx->bucket_begin, ctx->padded_d);
+    if (rc == COCOD_OK) rc = validate(cfg, ctx->padded_d);
+    if (rc != COCOD_OK) { delete ctx; return rc; }
+
+    ctx->cfg = *cfg;
+    ctx->cfg.tensor_numel = nullptr;
+    ctx->dry = (cfg->flags & COCOD_FLAG_DRY_RUN) != 0;
+    ctx->s_compute = static_cast<hipStream_t>(cfg->compute_stream);
+    ctx->s_avg = static_cast<hipStream_t>(cfg->avg_stream);
+    ctx->live = cfg->xA;
+    ctx->spare = cfg->xB;
+
+    uint64_t global = 0;
+    for (size_t t = 0; t < ctx->tensor_numel.size(); ++t) {
+        for (uint64_t off = 0; off < ctx->tensor_numel[t]; off += cocod::kChunkElems) {
+            const uint64_t left = ctx->tensor_numel[t] - off;
+            Chunk ck{};
+            ck.mem_off = ctx->tensor_offset[t] + off;
+            ck.glob_off = global + off;
+            ck.n = static_cast<uint32_t>(left < cocod::kChunkElems ? left : cocod::kChunkElems);
+            ctx->chunks.push_back(ck);
+        }
+        global += ctx->tensor_numel[t];
+    }
+    if (ctx->chunks.size() > 0x7fffffffull) { delete ctx; return fail(nullptr, COCOD_ERR_INVALID, "too many chunks"); }
+
+    std::vector<float> weights;
+    if (cfg->weights) weights.assign(cfg->weights, cfg->weights + cfg->W);
+    ctx->cfg.weights = nullptr;
+
+    if (!ctx->dry) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&ctx->d_chunks), ctx->chunks.size() * sizeof(Chunk));
+        if (e == hipSuccess)
+            e = hipMemcpy(ctx->d_chunks, ctx->chunks.data(), ctx->chunks.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !weights.empty()) {
+            e = hipMalloc(reinterpret_cast<void **>(&ctx->d_weights), weights.size() * sizeof(float));
+            if (e == hipSuccess)
+                e = hipMemcpy(ctx->d_weights, weights.data(), weights.size() * sizeof(float), hipMemcpyHostToDevice);
+        }
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_snap, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_mean, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            const int code = (e == hipErrorOutOfMemory) ? COCOD_ERR_NOMEM : COCOD_ERR_HIP;
+            fail(nullptr, code, "cocod_create: %s", hipGetErrorString(e));
+            release(ctx);
+            return code;
+        }
+    }
+    *out = ctx;
+    return COCOD_OK;
+}
+
+int cocod_destroy(cocod_ctx *ctx)
+{
+    if (!ctx) return COCOD_OK;
+    int rc = COCOD_OK;
+    if (!ctx->dry) {
+        hipError_t e = hipStreamSynchronize(ctx->s_avg);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->s_compute);
+        if (e != hipSuccess) rc = hip_fail(nullptr, e, "cocod_destroy");
+    }
+    release(ctx);
+    return rc;
+}
+
+int cocod_sync(cocod_ctx *ctx)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (ctx->dry) return COCOD_OK;
+    COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_avg));
+    COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    return COCOD_OK;
+}
+
+int cocod_local_steps(cocod_ctx *ctx, int k)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (k < 0) return fail(ctx, COCOD_ERR_INVALID, "k must be >= 0, got %d", k);
+    if (ctx->step + static_cast<uint64_t>(k) > 0xffffffffull)
+        return fail(ctx, COCOD_ERR_INVALID, "step counter would exceed 2^32 - 1");
+    for (int s = 0; s < k; ++s) {
+        // Keep the stored models intact: the first step of an open round reads them and
+        // writes the spare buffer, which then becomes the live one.
+        float *dst = ctx->store_pending ? ctx->spare : ctx->live;
+        if (!ctx->dry) {
+            cocod::StepParams p{};
+            p.table = ctx->d_chunks;
+            p.n_chunks = static_cast<uint32_t>(ctx->chunks.size());
+            p.W = ctx->cfg.W;
+            p.stride = ctx->cfg.stride;
+            p.x_in = ctx->live;
+            p.x_out = dst;
+            p.v = ctx->cfg.v;
+            p.h = ctx->cfg.h;
+            p.c = ctx->cfg.c;
+            p.lr = ctx->cfg.lr;
+            p.momentum = ctx->cfg.momentum;
+            p.weight_decay = ctx->cfg.weight_decay;
+            p.sigma = ctx->cfg.noise_sigma;
+            p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
+            p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
+            p.step = static_cast<uint32_t>(ctx->step);
+            COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p));
+        }
+        if (ctx->store_pending) {
+            ctx->spare = ctx->live;
+            ctx->live = dst;
+            ctx->store_pending = false;
+        }
+        ctx->step += 1;
+    }
+    return COCOD_OK;
+}
+
+int cocod_average_begin(cocod_ctx *ctx)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_average_begin: a round is already open");
+    ctx->snap = ctx->live;
+    if (!ctx->dry && ctx->schedule == COCOD_SCHED_OVERLAP) {
+        const bool two_streams = ctx->s_avg != ctx->s_compute;
+        if (two_streams) {
+            COCOD_HIP(ctx, hipEventRecord(ctx->ev_snap, ctx->s_compute));
+            COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_avg, ctx->ev_snap, 0));
+        }
+        const int rc = enqueue_mean(ctx, ctx->s_avg);
+        if (rc != COCOD_OK) return rc;
+        if (two_streams) COCOD_HIP(ctx, hipEventRecord(ctx->ev_mean, ctx->s_avg));
+    }
+    ctx->averaging = true;
+    ctx->store_pending = true;
+    return COCOD_OK;
+}
+
+int cocod_average_end_apply(cocod_ctx *ctx)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (!ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_average_end_apply: no round is open");
+    if (!ctx->dry) {
+        const size_t n_buckets = ctx->bucket_begin.size() - 1;
+        if (ctx->schedule == COCOD_SCHED_FUSED) {
+            for (size_t b = 0; b < n_buckets; ++b)
+                COCOD_HIP(ctx, cocod::launch_mean_correct(ctx->s_compute, ctx->live, ctx->snap, ctx->cfg.stride, ctx->cfg.W,
+                                                          ctx->bucket_begin[b], ctx->bucket_begin[b + 1], ctx->d_weights,
+                                                          ctx->cfg.mean));
+        } else {
+            if (ctx->schedule == COCOD_SCHED_SERIAL) {
+                const int rc = enqueue_mean(ctx, ctx->s_compute);
+                if (rc != COCOD_OK) return rc;
+            } else if (ctx->s_avg != ctx->s_compute) {
+                COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));   // the join
+            }
+            for (size_t b = 0; b < n_buckets; ++b)
+                COCOD_HIP(ctx, cocod::launch_correct(ctx->s_compute, ctx->live, ctx->snap, ctx->cfg.mean, ctx->cfg.stride,
+                                                     ctx->cfg.W, ctx->bucket_begin[b], ctx->bucket_begin[b + 1]));
+        }
+    }
+    ctx->averaging = false;
+    ctx->store_pending = false;
+    ctx->snap = nullptr;
+    return COCOD_OK;
+}
+
+int cocod_set_schedule(cocod_ctx *ctx, int schedule)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (schedule != COCOD_SCHED_OVERLAP && schedule != COCOD_SCHED_SERIAL && schedule != COCOD_SCHED_FUSED)
+        return fail(ctx, COCOD_ERR_INVALID, "unknown schedule %d", schedule);
+    if (ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_set_schedule: not while a round is open");
+    ctx->schedule = schedule;
+    return COCOD_OK;
+}
+
+int cocod_set_lr(cocod_ctx *ctx, float lr)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (!std::isfinite(lr)) return fail(ctx, COCOD_ERR_INVALID, "lr is not finite");
+    ctx->cfg.lr = lr;
+    return COCOD_OK;
+}
+
+int cocod_get_step(const cocod_ctx *ctx, uint64_t *step)
+{
+    if (!ctx || !step) return fail(nullptr, COCOD_ERR_INVALID, "ctx and step must not be NULL");
+    *step = ctx->step;
+    return COCOD_OK;
+}
+
+int cocod_set_step(cocod_ctx *ctx, uint64_t step)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (step > 0xffffffffull) return fail(ctx, COCOD_ERR_INVALID, "step must be < 2^32");
+    ctx->step = step;
+    return COCOD_OK;
+}
+
+int cocod_live_model(const cocod_ctx *ctx, float **x_live)
+{
+    if (!ctx || !x_live) return fail(nullptr, COCOD_ERR_INVALID, "ctx and x_live must not be NULL");
+    *x_live = ctx->live;
+    return COCOD_OK;
+}
+
+int cocod_is_averaging(const cocod_ctx *ctx)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    return ctx->averaging ? 1 : 0;
+}
+
+int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks, uint32_t *n_buckets)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (padded_d) *padded_d = ctx->padded_d;
+    if (n_chunks) *n_chunks = static_cast<uint32_t>(ctx->chunks.size());
+    if (n_buckets) *n_buckets = static_cast<uint32_t>(ctx->bucket_begin.size() - 1);
+    return COCOD_OK;
+}
+
+int cocod_fill_quadratic(cocod_ctx *ctx)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (ctx->cfg.grad != COCOD_GRAD_QUADRATIC) return fail(ctx, COCOD_ERR_INVALID, "not a quadratic-gradient context");
+    if (ctx->dry) return COCOD_OK;
+    COCOD_HIP(ctx, cocod::launch_fill_quadratic(ctx->s_compute, ctx->d_chunks, static_cast<uint32_t>(ctx->chunks.size()),
+                                                ctx->cfg.W, ctx->cfg.stride, ctx->padded_d,
+                                                const_cast<float *>(ctx->cfg.h), const_cast<float *>(ctx->cfg.c),
+                                                static_cast<uint32_t>(ctx->cfg.seed),
+                                                static_cast<uint32_t>(ctx->cfg.seed >> 32)));
+    return COCOD_OK;
+}
+
+int cocod_debug_normals(void *stream, uint64_t seed, uint32_t tag, uint32_t worker, uint32_t step, uint64_t j0,
+                        uint64_t n, int fast, float *out)
+{
+    if (n == 0) return COCOD_OK;
+    if (!out) return fail(nullptr, COCOD_ERR_INVALID, "out is NULL");
+    if (j0 + n > (1ull << 34)) return fail(nullptr, COCOD_ERR_INVALID, "index range exceeds 2^34");
+    const hipError_t e = cocod::launch_debug_normals(static_cast<hipStream_t>(stream), static_cast<uint32_t>(seed),
+                                                     static_cast<uint32_t>(seed >> 32), tag, worker, step, j0, n, fast, out);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "cocod_debug_normals");
+    return COCOD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,153 @@
+// Step I and line 6 of Algorithm 1 (CoCoD-SGD) on one GPU.
+//
+//   wmean         mean_j = sum_i p_i snap_ij           (the paper's all-reduce between workers)
+//   correct       x_ij   = mean_j + (x_ij - snap_ij)   (line 6)
+//   mean_correct  both in one pass (sequential schedule, nothing to overlap)
+//
+// Models are worker-major [W][stride], so the reduction runs along the SLOW axis:
+// a thread owns one 16-byte column quad and walks the W rows with independent
+// 16-byte loads; consecutive lanes own consecutive quads, so every wave load is
+// 1 KiB contiguous.  The sum is taken in worker order 0..W-1 in fp32, which fixes
+// the result bit for bit regardless of launch shape or schedule.
+// For line 6 the same thread serves all W workers of its column, so the mean is
+// read once per column instead of once per worker (12 + 4/W bytes per parameter).
+#include "internal.hpp"
+
+namespace cocod {
+namespace {
+
+constexpr uint32_t kAvgThreads = 256;
+constexpr int kRowBatch = 8;   // independent row loads in flight per thread
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ void st4(float *p, const float4 &a) { *reinterpret_cast<float4 *>(p) = a; }
+
+// Ordered weighted sum over the rows of one column quad.
+template <bool WEIGHTED>
+__device__ __forceinline__ float4 column_mean(const float *col, uint64_t stride, uint32_t W, const float *weights)
+{
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint32_t i = 0;
+    for (; i + kRowBatch <= W; i += kRowBatch) {
+        float4 r[kRowBatch];
+        #pragma unroll
+        for (int b = 0; b < kRowBatch; ++b) r[b] = ld4(col + static_cast<uint64_t>(i + b) * stride);
+        #pragma unroll
+        for (int b = 0; b < kRowBatch; ++b) {
+            const float pw = WEIGHTED ? weights[i + b] : 1.0f;
+            acc.x += pw * r[b].x; acc.y += pw * r[b].y; acc.z += pw * r[b].z; acc.w += pw * r[b].w;
+        }
+    }
+    for (; i < W; ++i) {
+        const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
+        const float pw = WEIGHTED ? weights[i] : 1.0f;
+        acc.x += pw * r.x; acc.y += pw * r.y; acc.z += pw * r.z; acc.w += pw * r.w;
+    }
+    if (!WEIGHTED) {
+        const float inv = 1.0f / static_cast<float>(W);
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    }
+    return acc;
+}
+
+template <bool WEIGHTED>
+__global__ __launch_bounds__(kAvgThreads) void wmean_kernel(const float *snap, uint64_t stride, uint32_t W,
+                                                            uint64_t begin, uint64_t n_quads,
+                                                            const float *weights, float *mean)
+{
+    const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
+    if (quad >= n_quads) return;
+    const uint64_t e = begin + quad * 4;
+    st4(mean + e, column_mean<WEIGHTED>(snap + e, stride, W, weights));
+}
+
+__device__ __forceinline__ void correct_column(float *xcol, const float *scol, const float4 m, uint64_t stride, uint32_t W)
+{
+    constexpr int B = 4;
+    uint32_t i = 0;
+    for (; i + B <= W; i += B) {
+        float4 xr[B], sr[B];
+        #pragma unroll
+        for (int b = 0; b < B; ++b) {
+            xr[b] = ld4(xcol + static_cast<uint64_t>(i + b) * stride);
+            sr[b] = ld4(scol + static_cast<uint64_t>(i + b) * stride);
+        }
+        #pragma unroll
+        for (int b = 0; b < B; ++b) {
+            float4 o;
+            o.x = m.x + (xr[b].x - sr[b].x); o.y = m.y + (xr[b].y - sr[b].y);
+            o.z = m.z + (xr[b].z - sr[b].z); o.w = m.w + (xr[b].w - sr[b].w);
+            st4(xcol + static_cast<uint64_t>(i + b) * stride, o);
+        }
+    }
+    for (; i < W; ++i) {
+        const float4 xr = ld4(xcol + static_cast<uint64_t>(i) * stride);
+        const float4 sr = ld4(scol + static_cast<uint64_t>(i) * stride);
+        float4 o;
+        o.x = m.x + (xr.x - sr.x); o.y = m.y + (xr.y - sr.y);
+        o.z = m.z + (xr.z - sr.z); o.w = m.w + (xr.w - sr.w);
+        st4(xcol + static_cast<uint64_t>(i) * stride, o);
+    }
+}
+
+__global__ __launch_bounds__(kAvgThreads) void correct_kernel(float *x, const float *snap, const float *mean,
+                                                              uint64_t stride, uint32_t W, uint64_t begin,
+                                                              uint64_t n_quads)
+{
+    const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
+    if (quad >= n_quads) return;
+    const uint64_t e = begin + quad * 4;
+    correct_column(x + e, snap + e, ld4(mean + e), stride, W);
+}
+
+template <bool WEIGHTED>
+__global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, const float *snap, uint64_t stride,
+                                                                   uint32_t W, uint64_t begin, uint64_t n_quads,
+                                                                   const float *weights, float *mean)
+{
+    const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
+    if (quad >= n_quads) return;
+    const uint64_t e = begin + quad * 4;
+    const float4 m = column_mean<WEIGHTED>(snap + e, stride, W, weights);
+    st4(mean + e, m);
+    // the stored models are read a second time here; they were just touched, so this pass hits cache
+    correct_column(x + e, snap + e, m, stride, W);
+}
+
+inline uint32_t blocks_for(uint64_t n_quads) { return static_cast<uint32_t>((n_quads + kAvgThreads - 1) / kAvgThreads); }
+
+}  // namespace
+
+hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, uint32_t W, uint64_t begin,
+                        uint64_t end, const float *weights, float *mean)
+{
+    const uint64_t n_quads = (end - begin) / 4;
+    if (n_quads == 0) return hipSuccess;
+    const dim3 grid(blocks_for(n_quads)), block(kAvgThreads);
+    if (weights) hipLaunchKernelGGL((wmean_kernel<true>), grid, block, 0, stream, snap, stride, W, begin, n_quads, weights, mean);
+    else         hipLaunchKernelGGL((wmean_kernel<false>), grid, block, 0, stream, snap, stride, W, begin, n_quads, weights, mean);
+    return hipGetLastError();
+}
+
+hipError_t launch_correct(hipStream_t stream, float *x, const float *snap, const float *mean, uint64_t stride,
+                          uint32_t W, uint64_t begin, uint64_t end)
+{
+    const uint64_t n_quads = (end - begin) / 4;
+    if (n_quads == 0) return hipSuccess;
+    hipLaunchKernelGGL(correct_kernel, dim3(blocks_for(n_quads)), dim3(kAvgThreads), 0, stream, x, snap, mean,
+                       stride, W, begin, n_quads);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, uint64_t stride, uint32_t W,
+                               uint64_t begin, uint64_t end, const float *weights, float *mean)
+{
+    const uint64_t n_quads = (end - begin) / 4;
+    if (n_quads == 0) return hipSuccess;
+    const dim3 grid(blocks_for(n_quads)), block(kAvgThreads);
+    if (weights) hipLaunchKernelGGL((mean_correct_kernel<true>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+    else         hipLaunchKernelGGL((mean_correct_kernel<false>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+    return hipGetLastError();
+}
+
+}  // namespace cocod

@@ -1,0 +1,62 @@
+// Internal declarations shared by the host side of libcocod and its kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cocod {
+
+// One block of the local-step kernel serves one chunk: up to kChunkElems
+// consecutive elements of ONE tensor of one worker.
+constexpr uint32_t kChunkElems = 4096;
+constexpr uint32_t kStepThreads = 256;
+
+// Stream tags: fourth counter word of the generator, keeps random streams disjoint.
+enum : uint32_t { kTagNoise = 0, kTagH = 1, kTagC = 2, kTagMlpX = 4, kTagMlpY = 5 };
+
+struct Chunk {
+    uint64_t mem_off;   // element offset inside a worker's padded row (multiple of 4)
+    uint64_t glob_off;  // unpadded global parameter index of the chunk's first element
+    uint32_t n;         // real elements in the chunk (1 .. kChunkElems)
+    uint32_t reserved;
+};
+
+struct StepParams {
+    const Chunk *table;
+    uint32_t n_chunks;
+    uint32_t W;
+    uint64_t stride;
+    const float *x_in;   // models read by the step
+    float *x_out;        // models written by the step (== x_in for an in-place step)
+    float *v;            // momentum, unused when momentum == 0
+    const float *h;
+    const float *c;
+    float lr, momentum, weight_decay, sigma;
+    uint32_t key0, key1; // generator key (seed low, seed high)
+    uint32_t step;       // global step counter t
+};
+
+hipError_t launch_quad_step(hipStream_t stream, const StepParams &p);
+
+// mean[e] = sum_i p_i snap[i][e] for e in [begin, end) (both multiples of 4);
+// weights == nullptr means p_i = 1/W.
+hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, uint32_t W,
+                        uint64_t begin, uint64_t end, const float *weights, float *mean);
+
+// x[i][e] = mean[e] + (x[i][e] - snap[i][e])
+hipError_t launch_correct(hipStream_t stream, float *x, const float *snap, const float *mean,
+                          uint64_t stride, uint32_t W, uint64_t begin, uint64_t end);
+
+// both of the above in one pass; mean is still written
+hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, uint64_t stride,
+                               uint32_t W, uint64_t begin, uint64_t end, const float *weights,
+                               float *mean);
+
+hipError_t launch_fill_quadratic(hipStream_t stream, const Chunk *table, uint32_t n_chunks, uint32_t W,
+                                 uint64_t stride, uint64_t padded_d, float *h, float *c,
+                                 uint32_t key0, uint32_t key1);
+
+hipError_t launch_debug_normals(hipStream_t stream, uint32_t key0, uint32_t key1, uint32_t tag,
+                                uint32_t worker, uint32_t step, uint64_t j0, uint64_t n, int fast,
+                                float *out);
+
+}  // namespace cocod

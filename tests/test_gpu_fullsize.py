@@ -1,0 +1,79 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark times.
+
+The synthetic objective is separable, so the oracle can follow any set of columns on its own
+(pinned on the CPU by the subset-equals-full test): full vectors for a few rounds where the oracle
+still finishes in seconds, sampled columns (random draws plus every tile / tensor / bucket edge)
+for the full round counts."""
+import numpy as np
+import pytest
+
+import paper_1906_12043_amd as P
+import synth_inputs
+from oracle import cocod_oracle as orc
+from tests.gpu_harness import GpuWorkers, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+CHUNK = 4096
+
+
+def hyper_of(cfg):
+    return dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"],
+                noise_sigma=cfg["noise_sigma"], seed=cfg["seed"])
+
+
+def edge_columns(d, starts=()):
+    edges = [0, 1, 2, 3, 4, d - 5, d - 4, d - 3, d - 2, d - 1]
+    for s in list(starts) + [CHUNK, 2 * CHUNK, (d // CHUNK) * CHUNK]:
+        edges += [s - 2, s - 1, s, s + 1, s + 3, s + 4]
+    return edges
+
+
+def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0):
+    W, d = cfg["W"], cfg["d"]
+    starts = list(np.cumsum([0] + list(tensor_numel))[:-1]) if tensor_numel else []
+    cols = synth_inputs.sample_columns(cfg["seed"] + k, d, n_random, edge_columns(d, starts))
+    g = GpuWorkers(W, d, device_fill=True, tensor_numel=tensor_numel, bucket_bytes=bucket_bytes, **hyper_of(cfg))
+    h, c = orc.fill_quadratic(cfg["seed"], W, idx=cols)
+    hg, cg = g.data(cols.astype(np.int64))
+    assert np.array_equal(hg, h) and np.max(np.abs(cg.astype(np.float64) - c)) < 2e-6
+    o = orc.QuadraticOracle(h, c, idx=cols, **hyper_of(cfg))
+    for _ in range(cfg["rounds"]):
+        g.ctx.round(k)
+        o.round(k)
+    ii = cols.astype(np.int64)
+    ex, ev, em = rel_err(g.x(ii), o.x), rel_err(g.vel(ii), o.v), rel_err(g.avg(ii), o.mean)
+    print("%d columns, k=%d, %d rounds: rel err x %.3g v %.3g mean %.3g" % (cols.size, k, cfg["rounds"], ex, ev, em))
+    g.close()
+    assert ex <= TOL and em <= TOL and ev <= 10 * TOL
+    return ex
+
+
+def test_resnet18_size_full_vector_three_rounds():
+    cfg = synth_inputs.CONFIGS["C2_resnet18"]
+    W, d, k = cfg["W"], cfg["d"], 2
+    h, c = synth_inputs.quadratic_data(cfg["seed"], W, d)
+    g = GpuWorkers(W, d, h=h, c=c, **hyper_of(cfg))
+    o = orc.QuadraticOracle(h, c, **hyper_of(cfg))
+    for r in range(3):
+        g.ctx.round(k); o.round(k)
+    ex, ev = rel_err(g.x(), o.x), rel_err(g.vel(), o.v)
+    print("C2 full vector, 3 rounds k=2: rel err x %.3g v %.3g" % (ex, ev))
+    g.close()
+    assert ex <= TOL and ev <= 10 * TOL
+
+
+@pytest.mark.parametrize("k", [1, 2, 4])
+def test_resnet18_size_fifty_rounds_sampled(k):
+    subset_parity(synth_inputs.CONFIGS["C2_resnet18"], k)
+
+
+def test_vgg16_size_twenty_rounds_sampled():
+    subset_parity(synth_inputs.CONFIGS["C3_vgg16"], 2)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_bucketed_tensor_list_sampled(k):
+    cfg = synth_inputs.CONFIGS["C5_bucketed"]
+    sizes = synth_inputs.tensor_sizes(cfg["seed"], cfg["n_tensors"], cfg["d"], cfg["tensor_lo"], cfg["tensor_hi"])
+    subset_parity(cfg, k, n_random=50_000, tensor_numel=sizes, bucket_bytes=cfg["bucket_bytes"])

@@ -1,0 +1,195 @@
+"""GPU parity: the HIP library behind the C-ABI against the CPU oracle, element by element, on the
+same seeded inputs.  Bar (fp32 device arithmetic against the fp64 oracle): max |dx| <= 1e-5 (1 + |x|)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1906_12043_amd as P
+import synth_inputs
+from oracle import cocod_oracle as orc
+from tests.gpu_harness import GpuWorkers, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def hyper_of(cfg):
+    return dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"],
+                noise_sigma=cfg["noise_sigma"], seed=cfg["seed"])
+
+
+def check_state(gpu, o, cols=None, tol=TOL, what=""):
+    ex = rel_err(gpu.x(cols), o.x)
+    assert ex <= tol, "%s x: %.3g" % (what, ex)
+    if o.v is not None:
+        ev = rel_err(gpu.vel(cols), o.v)
+        assert ev <= 10 * tol, "%s v: %.3g" % (what, ev)      # v is ~1/lr times more sensitive than x
+    return ex
+
+
+# ---- the generator ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("fast,bound", [(1, 2e-5), (0, 2e-6)])
+def test_device_normals_match_oracle(fast, bound):
+    seed, n, j0 = 0xABCDEF0123456789, 1 << 18, 12345
+    out = torch.empty(n, device="cuda:0")
+    P.debug_normals(None, seed, orc.TAG_NOISE, 3, 17, j0, n, fast, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    want = orc.normals(seed, orc.TAG_NOISE, 3, 17, j0, n)
+    err = np.max(np.abs(got - want))
+    print("max |z_gpu - z_oracle| fast=%d: %.3g" % (fast, err))
+    assert err < bound
+
+
+def test_device_fill_matches_oracle():
+    W, d = 3, 10007
+    g = GpuWorkers(W, d, device_fill=True, lr=0.1, seed=0x1234567887654321)
+    h, c = g.data()
+    ho, co = orc.fill_quadratic(0x1234567887654321, W, d)
+    assert np.array_equal(h, ho)
+    assert np.max(np.abs(c.astype(np.float64) - co)) < 2e-6
+    assert float(g.h[:, d:g.padded].abs().max()) == 0.0      # alignment pads are zeroed
+    g.close()
+
+
+# ---- full-vector parity ------------------------------------------------------------------------
+
+def test_tiny_config_every_round():
+    cfg = synth_inputs.CONFIGS["C1_tiny"]
+    W, d, k = cfg["W"], cfg["d"], cfg["k"][0]
+    h, c = synth_inputs.quadratic_data(cfg["seed"], W, d)
+    g = GpuWorkers(W, d, h=h, c=c, **hyper_of(cfg))
+    o = orc.QuadraticOracle(h, c, **hyper_of(cfg))
+    worst = 0.0
+    for r in range(cfg["rounds"]):
+        g.ctx.round(k); o.round(k)
+        worst = max(worst, check_state(g, o, what="round %d" % r))
+        assert rel_err(g.avg(), o.mean) <= TOL
+    assert g.ctx.get_step() == o.step == cfg["rounds"] * k
+    print("C1 worst rel err %.3g" % worst)
+    g.close()
+
+
+@pytest.mark.parametrize("W,d,mu,wd,sigma,k", [
+    (1, 1, 0.0, 0.0, 0.01, 2), (1, 5, 0.9, 5e-4, 0.01, 3), (3, 3, 0.9, 0.0, 0.0, 1), (2, 4, 0.5, 0.01, 0.1, 4),
+    (4, 4097, 0.9, 5e-4, 0.01, 2), (16, 10007, 0.9, 5e-4, 0.01, 2), (5, 12289, 0.0, 0.0, 0.01, 3),
+    (64, 4100, 0.9, 5e-4, 0.01, 1), (7, 8192, 0.9, 0.0, 0.0, 8),
+])
+def test_small_shapes_ragged_tails(W, d, mu, wd, sigma, k):
+    hyper = dict(lr=0.05, momentum=mu, weight_decay=wd, noise_sigma=sigma, seed=1000 + d)
+    h, c = synth_inputs.quadratic_data(d, W, d)
+    x0 = np.random.default_rng(d).standard_normal(d).astype(np.float32)
+    g = GpuWorkers(W, d, h=h, c=c, x0=x0, extra_stride=8, **hyper)
+    o = orc.QuadraticOracle(h, c, x0, **hyper)
+    for r in range(4):
+        g.ctx.round(k); o.round(k)
+        check_state(g, o, what="round %d" % r)
+    g.close()
+
+
+def test_steps_outside_a_round_and_zero_step_round():
+    W, d = 4, 5000
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=5)
+    h, c = synth_inputs.quadratic_data(9, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, **hyper)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    g.ctx.local_steps(3); o.local_steps(3)                 # plain local SGD
+    check_state(g, o, what="local only")
+    g.ctx.average_begin(); g.ctx.average_end_apply()       # pure averaging: every worker lands on the mean
+    o.average_begin(); o.average_end_apply()
+    check_state(g, o, what="zero-step round")
+    x = g.x()
+    assert np.array_equal(x[0], x[1]) and np.array_equal(x[0], x[3])
+    g.ctx.average_begin(); g.ctx.local_steps(1); g.ctx.local_steps(2); g.ctx.average_end_apply()
+    o.average_begin(); o.local_steps(3); o.average_end_apply()
+    check_state(g, o, what="split calls")
+    g.close()
+
+
+def test_single_worker_first_round_is_exactly_plain_sgd():
+    """N = 1 from x0 = 0: snapshot and mean are 0, so line 6 returns the local model bit for bit."""
+    d = 9000
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=3)
+    h, c = synth_inputs.quadratic_data(4, 1, d)
+    a = GpuWorkers(1, d, h=h, c=c, **hyper)
+    b = GpuWorkers(1, d, h=h, c=c, **hyper)
+    a.ctx.round(3)
+    b.ctx.local_steps(3)
+    assert torch.equal(a.x_raw()[:, :d], b.x_raw()[:, :d])
+    a.close(); b.close()
+
+
+def test_weighted_mean():
+    W, d, k = 4, 6001, 2
+    p = [0.125, 0.25, 0.25, 0.375]
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=0.0, noise_sigma=0.01, seed=8)
+    h, c = synth_inputs.quadratic_data(2, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, weights=p, **hyper)
+    o = orc.QuadraticOracle(h, c, weights=p, **hyper)
+    for r in range(3):
+        g.ctx.round(k); o.round(k)
+        check_state(g, o, what="round %d" % r)
+    g.close()
+
+
+# ---- schedules and layouts give the same bits ----------------------------------------------------
+
+def run_bits(W, d, rounds, k, schedule, two_streams, tensor_numel=None, bucket_bytes=0):
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=77)
+    h, c = synth_inputs.quadratic_data(6, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, two_streams=two_streams, tensor_numel=tensor_numel,
+                   bucket_bytes=bucket_bytes, **hyper)
+    g.ctx.set_schedule(schedule)
+    for _ in range(rounds):
+        g.ctx.round(k)
+    g.ctx.sync()
+    out = (g.live()[:, :d] if g.pos is None else g.live()[:, g.pos]).clone()
+    vel = (g.v[:, :d] if g.pos is None else g.v[:, g.pos]).clone()
+    g.close()
+    return out, vel
+
+
+def test_overlapped_round_is_bit_identical_to_serialised_rounds():
+    W, d, rounds, k = 8, 300_001, 6, 2
+    ref = run_bits(W, d, rounds, k, P.SCHED_OVERLAP, two_streams=False)
+    for schedule, two in [(P.SCHED_OVERLAP, True), (P.SCHED_SERIAL, True), (P.SCHED_FUSED, True), (P.SCHED_FUSED, False)]:
+        got = run_bits(W, d, rounds, k, schedule, two_streams=two)
+        assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]), (schedule, two)
+
+
+def test_packed_tensor_list_is_bit_identical_to_flat_and_matches_oracle():
+    W, rounds, k = 4, 3, 2
+    sizes = [5, 4096, 1, 3, 8191, 64, 4097, 2, 10000, 7]      # every start alignment, tails of 1..3
+    d = sum(sizes)
+    flat = run_bits(W, d, rounds, k, P.SCHED_OVERLAP, True)
+    packed = run_bits(W, d, rounds, k, P.SCHED_OVERLAP, True, tensor_numel=sizes, bucket_bytes=40000)
+    assert torch.equal(flat[0], packed[0]) and torch.equal(flat[1], packed[1])
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=77)
+    h, c = synth_inputs.quadratic_data(6, W, d)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    for _ in range(rounds):
+        o.round(k)
+    assert rel_err(packed[0].cpu().numpy().astype(np.float64), o.x) <= TOL
+
+
+def test_checkpoint_resume_is_bit_identical():
+    """State = models, momentum, step counter: restoring them continues the same trajectory."""
+    W, d, k = 4, 20_000, 2
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=21)
+    h, c = synth_inputs.quadratic_data(3, W, d)
+    a = GpuWorkers(W, d, h=h, c=c, **hyper)
+    for _ in range(4):
+        a.ctx.round(k)
+    want = a.x_raw()[:, :d].clone()
+    b = GpuWorkers(W, d, h=h, c=c, **hyper)
+    b.ctx.round(k); b.ctx.round(k)
+    x_mid, v_mid, step_mid = b.x_raw()[:, :d].cpu().numpy(), b.v[:, :d].cpu().numpy(), b.ctx.get_step()
+    b.close()
+    r = GpuWorkers(W, d, h=h, c=c, x0=x_mid, **hyper)
+    r.v[:, :d] = torch.from_numpy(v_mid).to(r.dev)
+    torch.cuda.synchronize()
+    r.ctx.set_step(step_mid)
+    r.ctx.round(k); r.ctx.round(k)
+    assert torch.equal(r.x_raw()[:, :d], want)
+    a.close(); r.close()
