@@ -32,30 +32,28 @@ def round_bytes(W, d, k):
     return W * d * (STEP_BYTES * k + 4 * (1 + 1 / W) + 12 + 4 / W)
 
 
-def time_rounds(ctx, torch, s_compute, k, rounds, warmup, want_step_events):
+def time_rounds(ctx, torch, k, rounds, warmup, want_step_times):
+    """Seconds per round over `rounds` timed rounds, and the average step-kernel duration in seconds
+    measured over the same rounds (the kernel's own start/stop timestamps on the compute stream)."""
     for _ in range(warmup):
         ctx.round(k)
     ctx.sync()
+    ctx.step_timing(rounds * k if want_step_times else 0)
     torch.cuda.synchronize()
-    events = []
     t0 = time.perf_counter()
     for _ in range(rounds):
         ctx.average_begin()
-        for _s in range(k):
-            if want_step_events:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(s_compute)
-                ctx.local_steps(1)
-                b.record(s_compute)
-                events.append((a, b))
-            else:
-                ctx.local_steps(1)
+        ctx.local_steps(k)
         ctx.average_end_apply()
     ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    step_ms = [a.elapsed_time(b) for a, b in events]
-    return elapsed / rounds, step_ms
+    step_s = None
+    if want_step_times:
+        total_ms, n = ctx.step_timing_read()
+        step_s = total_ms / max(n, 1) / 1e3
+        ctx.step_timing(0)
+    return elapsed / rounds, step_s
 
 
 def cpu_baseline(cfg, k):
@@ -122,8 +120,7 @@ def main():
     ctx.sync()
 
     k = args.k
-    per_round, step_ms = time_rounds(ctx, torch, s_compute, k, args.steps, args.warmup, True)
-    avg_step_s = sum(step_ms) / len(step_ms) / 1e3
+    per_round, avg_step_s = time_rounds(ctx, torch, k, args.steps, args.warmup, True)
     achieved = STEP_BYTES * W * d / avg_step_s / 1e9
     out = {
         "metric": "worker-param-updates/s per CoCoD round (W=16, d=11.2M)",
@@ -141,20 +138,20 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "quad_step_kernel<momentum, noise>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": STEP_TRAFFIC_BYTES, "avg_launch_ms": avg_step_s * 1e3,
-                     "launches_timed": len(step_ms), "algorithmic_bytes_per_launch": STEP_BYTES * W * d},
+                     "launches_timed": args.steps * k, "algorithmic_bytes_per_launch": STEP_BYTES * W * d},
     }
     if not args.headline_only:
         sweep = {}
         for kk in cfg["k"]:
-            pr, sm = time_rounds(ctx, torch, s_compute, kk, args.steps, 2, True)
+            pr, sm = time_rounds(ctx, torch, kk, args.steps, 2, True)
             sweep["k=%d" % kk] = {"ms_per_round": pr * 1e3, "updates_per_s": W * d * kk / pr,
                                   "round_GBps": round_bytes(W, d, kk) / pr / 1e9,
-                                  "step_kernel_ms": sum(sm) / len(sm)}
+                                  "step_kernel_ms": sm * 1e3}
         out["k_sweep"] = sweep
         sched = {}
         for name, code in (("serial", P.SCHED_SERIAL), ("fused", P.SCHED_FUSED), ("overlap", P.SCHED_OVERLAP)):
             ctx.set_schedule(code)
-            pr, _ = time_rounds(ctx, torch, s_compute, k, args.steps, 2, False)
+            pr, _ = time_rounds(ctx, torch, k, args.steps, 2, False)
             sched[name] = pr * 1e3
         out["schedule_ms_per_round"] = sched
     ctx.close()

@@ -17,8 +17,8 @@
  *     unless stated otherwise; no exception crosses the boundary.
  *   - "device" pointers are HIP device memory, "host" pointers ordinary memory.
  *   - every call only ENQUEUES work on the caller's streams; nothing waits for
- *     the GPU except cocod_create (with COCOD_FLAG_SELFTEST never), cocod_sync
- *     and cocod_destroy.
+ *     the GPU except cocod_sync, cocod_step_timing_read and cocod_destroy
+ *     (cocod_create copies its small tables synchronously).
  *   - the caller owns all large device buffers and both streams; they must
  *     outlive the context.  The context owns its chunk table, two events, the
  *     optional weight vector and the MLP work space.
@@ -177,6 +177,15 @@ int cocod_is_averaging(const cocod_ctx *ctx);
 /* Number of chunks of the step kernel's chunk table and number of buckets (for inspection). */
 int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks, uint32_t *n_buckets);
 
+/*
+ * Measurement aid.  cocod_step_timing(ctx, n) with n > 0 makes the next n local-step kernel
+ * launches carry the runtime's own start/stop timestamps (events on compute_stream, owned by the
+ * context); n = 0 switches it off.  cocod_step_timing_read waits for compute_stream, returns the
+ * summed kernel durations and the number of launches measured since the last read, and rearms.
+ */
+int cocod_step_timing(cocod_ctx *ctx, int max_launches);
+int cocod_step_timing_read(cocod_ctx *ctx, double *total_ms, uint32_t *launches);
+
 /* Block the host until both streams have drained. */
 int cocod_sync(cocod_ctx *ctx);
 
@@ -196,6 +205,13 @@ int cocod_fill_quadratic(cocod_ctx *ctx);
  */
 int cocod_debug_normals(void *stream, uint64_t seed, uint32_t tag, uint32_t worker, uint32_t step,
                         uint64_t j0, uint64_t n, int fast, float *out);
+
+/*
+ * Measurement aid: plain streaming copy of n fp32 elements (n multiple of 4, both pointers device,
+ * 16-byte aligned, not overlapping) on `stream`.  A kernel of exactly known traffic (4n bytes read,
+ * 4n written) against which hardware memory counters are calibrated.  No context needed.
+ */
+int cocod_debug_copy(void *stream, const float *src, float *dst, uint64_t n);
 
 /* Last error text of ctx, or of the last failed cocod_create / context-free call when ctx is NULL.
    Never NULL; owned by the library; valid until the next call on the same context / thread. */

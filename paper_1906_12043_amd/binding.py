@@ -72,6 +72,9 @@ def lib():
             "cocod_is_averaging": ([vp], i32),
             "cocod_get_plan": ([vp, P(u64), P(u32), P(u32)], i32),
             "cocod_fill_quadratic": ([vp], i32),
+            "cocod_step_timing": ([vp, i32], i32),
+            "cocod_step_timing_read": ([vp, P(C.c_double), P(u32)], i32),
+            "cocod_debug_copy": ([vp, vp, vp, u64], i32),
             "cocod_debug_normals": ([vp, u64, u32, u32, u32, u64, u64, i32, vp], i32),
         }
         for name, (args, res) in sigs.items():
@@ -112,6 +115,10 @@ def plan_layout(d, tensor_numel=None, bucket_bytes=0):
 
 def debug_normals(stream, seed, tag, worker, step, j0, n, fast, out):
     _check(lib().cocod_debug_normals(_addr(stream), seed, tag, worker, step, j0, n, int(fast), _addr(out)))
+
+
+def debug_copy(stream, src, dst, n):
+    _check(lib().cocod_debug_copy(_addr(stream), _addr(src), _addr(dst), n))
 
 
 # ---- the five entry points of the round, by their C names -----------------------------------
@@ -228,6 +235,15 @@ class Context:
         padded, chunks, buckets = C.c_uint64(), C.c_uint32(), C.c_uint32()
         _check(lib().cocod_get_plan(self.handle, C.byref(padded), C.byref(chunks), C.byref(buckets)), self.handle)
         return padded.value, chunks.value, buckets.value
+
+    def step_timing(self, max_launches):
+        return _check(lib().cocod_step_timing(self.handle, max_launches), self.handle)
+
+    def step_timing_read(self):
+        """(summed step-kernel milliseconds, launches measured) since the last read."""
+        total, n = C.c_double(), C.c_uint32()
+        _check(lib().cocod_step_timing_read(self.handle, C.byref(total), C.byref(n)), self.handle)
+        return total.value, n.value
 
     def fill_quadratic(self):
         return _check(lib().cocod_fill_quadratic(self.handle), self.handle)

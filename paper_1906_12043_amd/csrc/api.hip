@@ -33,6 +33,9 @@ struct cocod_ctx {
     int schedule = COCOD_SCHED_OVERLAP;
     uint64_t step = 0;                  // global step counter t
     bool dry = false;
+    bool timing = false;                // bracket step launches with start/stop events
+    std::vector<hipEvent_t> t_start, t_stop;   // event pool for step timing (owned)
+    size_t t_used = 0;
     std::string err;
 };
 
@@ -163,6 +166,8 @@ void release(cocod_ctx *ctx)
         if (ctx->d_weights) (void)hipFree(ctx->d_weights);
         if (ctx->ev_snap) (void)hipEventDestroy(ctx->ev_snap);
         if (ctx->ev_mean) (void)hipEventDestroy(ctx->ev_mean);
+        for (hipEvent_t e : ctx->t_start) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ctx->t_stop) (void)hipEventDestroy(e);
     }
     delete ctx;
 }
@@ -226,7 +231,7 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         for (uint64_t off = 0; off < ctx->tensor_numel[t]; off += cocod::kChunkElems) {
             const uint64_t left = ctx->tensor_numel[t] - off;
             Chunk ck{};
-            ck.mem_off = ctx->tensor_offset[t] + off;
+            ck.mem_quad = static_cast<uint32_t>((ctx->tensor_offset[t] + off) / 4);
             ck.glob_off = global + off;
             ck.n = static_cast<uint32_t>(left < cocod::kChunkElems ? left : cocod::kChunkElems);
             ctx->chunks.push_back(ck);
@@ -311,7 +316,13 @@ int cocod_local_steps(cocod_ctx *ctx, int k)
             p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
             p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
             p.step = static_cast<uint32_t>(ctx->step);
-            COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p));
+            hipEvent_t t0 = nullptr, t1 = nullptr;
+            if (ctx->timing && ctx->t_used < ctx->t_start.size()) {
+                t0 = ctx->t_start[ctx->t_used];
+                t1 = ctx->t_stop[ctx->t_used];
+                ctx->t_used += 1;
+            }
+            COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p, t0, t1));
         }
         if (ctx->store_pending) {
             ctx->spare = ctx->live;
@@ -427,6 +438,40 @@ int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks,
     return COCOD_OK;
 }
 
+int cocod_step_timing(cocod_ctx *ctx, int max_launches)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (max_launches < 0 || max_launches > (1 << 20)) return fail(ctx, COCOD_ERR_INVALID, "max_launches out of range");
+    ctx->timing = max_launches > 0;
+    ctx->t_used = 0;
+    if (ctx->dry) return COCOD_OK;
+    while (ctx->t_start.size() < static_cast<size_t>(max_launches)) {
+        hipEvent_t a = nullptr, b = nullptr;
+        COCOD_HIP(ctx, hipEventCreate(&a));
+        ctx->t_start.push_back(a);
+        COCOD_HIP(ctx, hipEventCreate(&b));
+        ctx->t_stop.push_back(b);
+    }
+    return COCOD_OK;
+}
+
+int cocod_step_timing_read(cocod_ctx *ctx, double *total_ms, uint32_t *launches)
+{
+    if (!ctx || !total_ms || !launches) return fail(nullptr, COCOD_ERR_INVALID, "ctx, total_ms and launches must not be NULL");
+    *total_ms = 0.0;
+    *launches = 0;
+    if (ctx->dry) return COCOD_OK;
+    COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    for (size_t i = 0; i < ctx->t_used && i < ctx->t_stop.size(); ++i) {
+        float ms = 0.0f;
+        COCOD_HIP(ctx, hipEventElapsedTime(&ms, ctx->t_start[i], ctx->t_stop[i]));
+        *total_ms += ms;
+        *launches += 1;
+    }
+    ctx->t_used = 0;
+    return COCOD_OK;
+}
+
 int cocod_fill_quadratic(cocod_ctx *ctx)
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
@@ -437,6 +482,17 @@ int cocod_fill_quadratic(cocod_ctx *ctx)
                                                 const_cast<float *>(ctx->cfg.h), const_cast<float *>(ctx->cfg.c),
                                                 static_cast<uint32_t>(ctx->cfg.seed),
                                                 static_cast<uint32_t>(ctx->cfg.seed >> 32)));
+    return COCOD_OK;
+}
+
+int cocod_debug_copy(void *stream, const float *src, float *dst, uint64_t n)
+{
+    if (n == 0) return COCOD_OK;
+    if (!src || !dst) return fail(nullptr, COCOD_ERR_INVALID, "src and dst must not be NULL");
+    if ((n & 3u) || !aligned16(src) || !aligned16(dst))
+        return fail(nullptr, COCOD_ERR_INVALID, "n must be a multiple of 4 and the pointers 16-byte aligned");
+    const hipError_t e = cocod::launch_copy(static_cast<hipStream_t>(stream), src, dst, n / 4);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "cocod_debug_copy");
     return COCOD_OK;
 }
 

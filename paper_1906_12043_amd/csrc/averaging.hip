@@ -19,8 +19,19 @@ namespace {
 constexpr uint32_t kAvgThreads = 256;
 constexpr int kRowBatch = 8;   // independent row loads in flight per thread
 
+typedef float f4v __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ __forceinline__ void st4(float *p, const float4 &a) { *reinterpret_cast<float4 *>(p) = a; }
+// models are streamed once per kernel and exceed the caches: non-temporal hint
+__device__ __forceinline__ float4 ld4_stream(const float *p)
+{
+    const f4v t = __builtin_nontemporal_load(reinterpret_cast<const f4v *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void st4_stream(float *p, const float4 &a)
+{
+    __builtin_nontemporal_store(f4v{a.x, a.y, a.z, a.w}, reinterpret_cast<f4v *>(p));
+}
 
 // Ordered weighted sum over the rows of one column quad.
 template <bool WEIGHTED>
@@ -31,7 +42,7 @@ __device__ __forceinline__ float4 column_mean(const float *col, uint64_t stride,
     for (; i + kRowBatch <= W; i += kRowBatch) {
         float4 r[kRowBatch];
         #pragma unroll
-        for (int b = 0; b < kRowBatch; ++b) r[b] = ld4(col + static_cast<uint64_t>(i + b) * stride);
+        for (int b = 0; b < kRowBatch; ++b) r[b] = ld4_stream(col + static_cast<uint64_t>(i + b) * stride);
         #pragma unroll
         for (int b = 0; b < kRowBatch; ++b) {
             const float pw = WEIGHTED ? weights[i + b] : 1.0f;
@@ -39,7 +50,7 @@ __device__ __forceinline__ float4 column_mean(const float *col, uint64_t stride,
         }
     }
     for (; i < W; ++i) {
-        const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
+        const float4 r = ld4_stream(col + static_cast<uint64_t>(i) * stride);
         const float pw = WEIGHTED ? weights[i] : 1.0f;
         acc.x += pw * r.x; acc.y += pw * r.y; acc.z += pw * r.z; acc.w += pw * r.w;
     }
@@ -69,24 +80,24 @@ __device__ __forceinline__ void correct_column(float *xcol, const float *scol, c
         float4 xr[B], sr[B];
         #pragma unroll
         for (int b = 0; b < B; ++b) {
-            xr[b] = ld4(xcol + static_cast<uint64_t>(i + b) * stride);
-            sr[b] = ld4(scol + static_cast<uint64_t>(i + b) * stride);
+            xr[b] = ld4_stream(xcol + static_cast<uint64_t>(i + b) * stride);
+            sr[b] = ld4_stream(scol + static_cast<uint64_t>(i + b) * stride);
         }
         #pragma unroll
         for (int b = 0; b < B; ++b) {
             float4 o;
             o.x = m.x + (xr[b].x - sr[b].x); o.y = m.y + (xr[b].y - sr[b].y);
             o.z = m.z + (xr[b].z - sr[b].z); o.w = m.w + (xr[b].w - sr[b].w);
-            st4(xcol + static_cast<uint64_t>(i + b) * stride, o);
+            st4_stream(xcol + static_cast<uint64_t>(i + b) * stride, o);
         }
     }
     for (; i < W; ++i) {
-        const float4 xr = ld4(xcol + static_cast<uint64_t>(i) * stride);
-        const float4 sr = ld4(scol + static_cast<uint64_t>(i) * stride);
+        const float4 xr = ld4_stream(xcol + static_cast<uint64_t>(i) * stride);
+        const float4 sr = ld4_stream(scol + static_cast<uint64_t>(i) * stride);
         float4 o;
         o.x = m.x + (xr.x - sr.x); o.y = m.y + (xr.y - sr.y);
         o.z = m.z + (xr.z - sr.z); o.w = m.w + (xr.w - sr.w);
-        st4(xcol + static_cast<uint64_t>(i) * stride, o);
+        st4_stream(xcol + static_cast<uint64_t>(i) * stride, o);
     }
 }
 

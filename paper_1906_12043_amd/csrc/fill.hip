@@ -16,7 +16,7 @@ __global__ __launch_bounds__(kFillThreads) void fill_quadratic_kernel(const Chun
 {
     const Chunk ck = table[blockIdx.x];
     const uint32_t worker = blockIdx.y;
-    const uint64_t row = static_cast<uint64_t>(worker) * stride + ck.mem_off;
+    const uint64_t row = static_cast<uint64_t>(worker) * stride + static_cast<uint64_t>(ck.mem_quad) * 4;
     const uint32_t n_padded = (ck.n + 3u) & ~3u;       // a tensor's tail quad ends in alignment pads
     for (uint32_t e = threadIdx.x; e < n_padded; e += kFillThreads) {
         if (e >= ck.n) { h[row + e] = 0.0f; c[row + e] = 0.0f; continue; }
@@ -43,7 +43,27 @@ __global__ __launch_bounds__(kFillThreads) void debug_normals_kernel(uint32_t ke
     out[m] = z.z[j & 3u];
 }
 
+// Plain streaming copy of n_quads 16-byte quads: the known-size reference that hardware traffic
+// counters are calibrated against.
+__global__ __launch_bounds__(kFillThreads) void copy_kernel(const float *src, float *dst, uint64_t n_quads)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const uint64_t q = static_cast<uint64_t>(blockIdx.x) * kFillThreads + threadIdx.x;
+    if (q >= n_quads) return;
+    const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(src) + q);
+    __builtin_nontemporal_store(t, reinterpret_cast<f4 *>(dst) + q);
+}
+
 }  // namespace
+
+hipError_t launch_copy(hipStream_t stream, const float *src, float *dst, uint64_t n_quads)
+{
+    if (n_quads == 0) return hipSuccess;
+    const uint64_t blocks = (n_quads + kFillThreads - 1) / kFillThreads;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kFillThreads), 0, stream, src, dst, n_quads);
+    return hipGetLastError();
+}
 
 hipError_t launch_fill_quadratic(hipStream_t stream, const Chunk *table, uint32_t n_chunks, uint32_t W,
                                  uint64_t stride, uint64_t padded_d, float *h, float *c, uint32_t key0,

@@ -6,19 +6,19 @@
 namespace cocod {
 
 // One block of the local-step kernel serves one chunk: up to kChunkElems
-// consecutive elements of ONE tensor of one worker.
-constexpr uint32_t kChunkElems = 4096;
+// consecutive elements of ONE tensor of one worker, one 16-byte quad per thread.
 constexpr uint32_t kStepThreads = 256;
+constexpr uint32_t kChunkElems = kStepThreads * 4;
 
 // Stream tags: fourth counter word of the generator, keeps random streams disjoint.
 enum : uint32_t { kTagNoise = 0, kTagH = 1, kTagC = 2, kTagMlpX = 4, kTagMlpY = 5 };
 
 struct Chunk {
-    uint64_t mem_off;   // element offset inside a worker's padded row (multiple of 4)
     uint64_t glob_off;  // unpadded global parameter index of the chunk's first element
+    uint32_t mem_quad;  // 16-byte quad offset inside a worker's padded row (element offset / 4)
     uint32_t n;         // real elements in the chunk (1 .. kChunkElems)
-    uint32_t reserved;
 };
+static_assert(sizeof(Chunk) == 16, "one 16-byte scalar load per block");
 
 struct StepParams {
     const Chunk *table;
@@ -35,7 +35,9 @@ struct StepParams {
     uint32_t step;       // global step counter t
 };
 
-hipError_t launch_quad_step(hipStream_t stream, const StepParams &p);
+// start / stop: optional events that receive the kernel's own begin / end timestamps
+hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start = nullptr,
+                            hipEvent_t stop = nullptr);
 
 // mean[e] = sum_i p_i snap[i][e] for e in [begin, end) (both multiples of 4);
 // weights == nullptr means p_i = 1/W.
@@ -54,6 +56,8 @@ hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, 
 hipError_t launch_fill_quadratic(hipStream_t stream, const Chunk *table, uint32_t n_chunks, uint32_t W,
                                  uint64_t stride, uint64_t padded_d, float *h, float *c,
                                  uint32_t key0, uint32_t key1);
+
+hipError_t launch_copy(hipStream_t stream, const float *src, float *dst, uint64_t n_quads);
 
 hipError_t launch_debug_normals(hipStream_t stream, uint32_t key0, uint32_t key1, uint32_t tag,
                                 uint32_t worker, uint32_t step, uint64_t j0, uint64_t n, int fast,

@@ -5,10 +5,18 @@
 // The gradient is never written to memory: the kernel reads x, v, h, c and writes
 // x, v (24 bytes per parameter; 16 when mu = 0 and v is untouched).
 //
-// Work decomposition: grid = (chunks, workers).  A chunk is up to 4096 consecutive
+// Work decomposition: grid = (chunks, workers).  A chunk is up to 1024 consecutive
 // elements of one tensor (multi-tensor apply: the chunk table maps a block to its
 // tensor slice, so one launch covers a whole parameter list).  A thread owns one
-// 16-byte quad per unrolled pass; a wave reads 1 KiB contiguous per array per pass.
+// 16-byte quad; a wave moves 1 KiB contiguous per array.  Small blocks with one
+// quad per thread measured faster on MI355X than fewer, longer-running blocks.
+//
+// Memory path: every array is streamed exactly once per step and is far larger
+// than the caches, so all accesses carry the non-temporal hint.  Accesses go
+// through buffer instructions whose descriptor covers exactly the chunk: lanes
+// past the chunk's end read zeros and their stores are dropped by the hardware
+// range check, so there is no divergent tail code.
+//
 // The generator's 128-bit block is keyed by the UNPADDED global parameter index, so
 // results do not depend on how tensors are packed; when a tensor starts at a global
 // index that is not a multiple of 4, a thread's quad straddles two generator blocks
@@ -16,114 +24,92 @@
 #include "internal.hpp"
 #include "philox.hpp"
 
+#include <hip/hip_ext.h>
+
 namespace cocod {
 namespace {
 
-constexpr int kUnroll = kChunkElems / (kStepThreads * 4);   // quads per thread
-static_assert(kUnroll * kStepThreads * 4 == kChunkElems, "chunk must split evenly");
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
-__device__ __forceinline__ void st4(float *p, const float4 &a) { *reinterpret_cast<float4 *>(p) = a; }
+constexpr int kAuxNonTemporal = 2;   // cache-policy bits of the buffer instructions: nt
+
+// Raw buffer descriptor over `bytes` bytes starting at p (stride 0, 32-bit data format).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const float *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ f4 load_quad(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, static_cast<int>(byte_off), 0, kAuxNonTemporal));
+}
+__device__ __forceinline__ void store_quad(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f4 a)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, a), r, static_cast<int>(byte_off), 0, kAuxNonTemporal);
+}
 
 // Four normals for the thread's quad whose first element has global index 4*q + shift.
-__device__ __forceinline__ Normals4 noise_for_quad(uint64_t q, uint32_t shift, const StepParams &p, uint32_t worker)
+__device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const StepParams &p, uint32_t worker)
 {
     const Normals4 a = box_muller_fast(
         philox4x32_10(static_cast<uint32_t>(q), p.step, worker, kTagNoise, p.key0, p.key1));
-    if (shift == 0) return a;                               // block-uniform branch
+    if (shift == 0) return f4{a.z[0], a.z[1], a.z[2], a.z[3]};          // block-uniform branch
     const Normals4 b = box_muller_fast(
         philox4x32_10(static_cast<uint32_t>(q + 1), p.step, worker, kTagNoise, p.key0, p.key1));
-    Normals4 out;
-    if (shift == 1)      { out.z[0] = a.z[1]; out.z[1] = a.z[2]; out.z[2] = a.z[3]; out.z[3] = b.z[0]; }
-    else if (shift == 2) { out.z[0] = a.z[2]; out.z[1] = a.z[3]; out.z[2] = b.z[0]; out.z[3] = b.z[1]; }
-    else                 { out.z[0] = a.z[3]; out.z[1] = b.z[0]; out.z[2] = b.z[1]; out.z[3] = b.z[2]; }
-    return out;
-}
-
-template <bool HAS_V>
-__device__ __forceinline__ void update_one(float &x, float &v, float h, float c, float noise, const StepParams &p)
-{
-    float g = h * (x - c) + noise;
-    g = g + p.weight_decay * x;
-    if (HAS_V) {
-        v = p.momentum * v + g;
-        g = v;
-    }
-    x = x - p.lr * g;
-}
-
-template <bool HAS_V, bool NOISE, bool FULL>
-__device__ __forceinline__ void process_chunk(const StepParams &p, const Chunk &ck, uint32_t worker)
-{
-    const uint64_t row = static_cast<uint64_t>(worker) * p.stride + ck.mem_off;
-    const float *xin = p.x_in + row;
-    float *xout = p.x_out + row;
-    float *vp = HAS_V ? p.v + row : nullptr;
-    const float *hp = p.h + row;
-    const float *cp = p.c + row;
-    const uint32_t shift = static_cast<uint32_t>(ck.glob_off & 3u);
-    const uint64_t q_base = ck.glob_off >> 2;
-
-    float4 X[kUnroll], V[kUnroll], H[kUnroll], Cc[kUnroll];
-    bool live[kUnroll];
-    #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        const uint32_t e = (u * kStepThreads + threadIdx.x) * 4;
-        live[u] = FULL || e < ck.n;
-        if (live[u]) {
-            X[u] = ld4(xin + e);
-            if (HAS_V) V[u] = ld4(vp + e);
-            H[u] = ld4(hp + e);
-            Cc[u] = ld4(cp + e);
-        }
-    }
-    #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        if (!live[u]) continue;
-        const uint32_t e = (u * kStepThreads + threadIdx.x) * 4;
-        Normals4 nz;
-        if (NOISE) {
-            nz = noise_for_quad(q_base + (e >> 2), shift, p, worker);
-            #pragma unroll
-            for (int i = 0; i < 4; ++i) nz.z[i] *= p.sigma;
-        } else {
-            nz.z[0] = nz.z[1] = nz.z[2] = nz.z[3] = 0.0f;
-        }
-        float4 x = X[u];
-        float4 v = HAS_V ? V[u] : make_float4(0.f, 0.f, 0.f, 0.f);
-        update_one<HAS_V>(x.x, v.x, H[u].x, Cc[u].x, nz.z[0], p);
-        update_one<HAS_V>(x.y, v.y, H[u].y, Cc[u].y, nz.z[1], p);
-        update_one<HAS_V>(x.z, v.z, H[u].z, Cc[u].z, nz.z[2], p);
-        update_one<HAS_V>(x.w, v.w, H[u].w, Cc[u].w, nz.z[3], p);
-        if (!FULL && e + 4 > ck.n) {          // tensor tail: alignment pads keep their old values
-            const uint32_t keep = ck.n - e;   // 1..3 real elements
-            if (keep < 2) { x.y = X[u].y; if (HAS_V) v.y = V[u].y; }
-            if (keep < 3) { x.z = X[u].z; if (HAS_V) v.z = V[u].z; }
-            x.w = X[u].w; if (HAS_V) v.w = V[u].w;
-        }
-        st4(xout + e, x);
-        if (HAS_V) st4(vp + e, v);
-    }
+    if (shift == 1) return f4{a.z[1], a.z[2], a.z[3], b.z[0]};
+    if (shift == 2) return f4{a.z[2], a.z[3], b.z[0], b.z[1]};
+    return f4{a.z[3], b.z[0], b.z[1], b.z[2]};
 }
 
 template <bool HAS_V, bool NOISE>
 __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParams p)
 {
     const Chunk ck = p.table[blockIdx.x];
-    if (ck.n == kChunkElems) process_chunk<HAS_V, NOISE, true>(p, ck, blockIdx.y);
-    else                     process_chunk<HAS_V, NOISE, false>(p, ck, blockIdx.y);
+    const uint32_t worker = blockIdx.y;
+    const uint64_t row = static_cast<uint64_t>(worker) * p.stride + static_cast<uint64_t>(ck.mem_quad) * 4;
+    const uint32_t bytes = ((ck.n + 3u) & ~3u) * 4u;      // whole quads: a tensor's tail quad ends in pads
+    const __amdgpu_buffer_rsrc_t rx_in = make_rsrc(p.x_in + row, bytes);
+    const __amdgpu_buffer_rsrc_t rx_out = make_rsrc(p.x_out + row, bytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(HAS_V ? p.v + row : p.x_in + row, bytes);
+    const __amdgpu_buffer_rsrc_t rh = make_rsrc(p.h + row, bytes);
+    const __amdgpu_buffer_rsrc_t rc = make_rsrc(p.c + row, bytes);
+
+    const uint32_t e = threadIdx.x * 4;                   // first element of this thread's quad
+    const uint32_t off = e * 4;
+    const f4 x0 = load_quad(rx_in, off);
+    const f4 v0 = HAS_V ? load_quad(rv, off) : f4{0.f, 0.f, 0.f, 0.f};
+    const f4 h = load_quad(rh, off);
+    const f4 c = load_quad(rc, off);
+
+    f4 g = h * (x0 - c);
+    if (NOISE)
+        g += p.sigma * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, static_cast<uint32_t>(ck.glob_off & 3u), p, worker);
+    g += p.weight_decay * x0;
+    f4 v = v0;
+    if (HAS_V) { v = p.momentum * v0 + g; g = v; }
+    f4 x = x0 - p.lr * g;
+
+    if (e + 4 > ck.n && e < ck.n) {                       // tensor tail: alignment pads keep their old values
+        const uint32_t keep = ck.n - e;                   // 1..3 real elements
+        if (keep < 2) { x.y = x0.y; v.y = v0.y; }
+        if (keep < 3) { x.z = x0.z; v.z = v0.z; }
+        x.w = x0.w; v.w = v0.w;
+    }
+    store_quad(rx_out, off, x);
+    if (HAS_V) store_quad(rv, off, v);
 }
 
 }  // namespace
 
-hipError_t launch_quad_step(hipStream_t stream, const StepParams &p)
+hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
     const dim3 grid(p.n_chunks, p.W), block(kStepThreads);
     const bool has_v = p.momentum != 0.0f, noise = p.sigma != 0.0f;
-    if (has_v && noise)       hipLaunchKernelGGL((quad_step_kernel<true, true>), grid, block, 0, stream, p);
-    else if (has_v && !noise) hipLaunchKernelGGL((quad_step_kernel<true, false>), grid, block, 0, stream, p);
-    else if (noise)           hipLaunchKernelGGL((quad_step_kernel<false, true>), grid, block, 0, stream, p);
-    else                      hipLaunchKernelGGL((quad_step_kernel<false, false>), grid, block, 0, stream, p);
+    // start/stop (may be null) receive the kernel's own begin and end timestamps
+    if (has_v && noise)       hipExtLaunchKernelGGL((quad_step_kernel<true, true>), grid, block, 0, stream, start, stop, 0, p);
+    else if (has_v && !noise) hipExtLaunchKernelGGL((quad_step_kernel<true, false>), grid, block, 0, stream, start, stop, 0, p);
+    else if (noise)           hipExtLaunchKernelGGL((quad_step_kernel<false, true>), grid, block, 0, stream, start, stop, 0, p);
+    else                      hipExtLaunchKernelGGL((quad_step_kernel<false, false>), grid, block, 0, stream, start, stop, 0, p);
     return hipGetLastError();
 }
 

@@ -174,11 +174,11 @@ def test_round_state_machine_and_buffer_rotation():
 
 def test_plan_of_context():
     with dry(d=10000) as ctx:
-        assert ctx.get_plan() == (10000, 3, 1)      # 4096 + 4096 + 1808
+        assert ctx.get_plan() == (10000, 10, 1)     # 9 x 1024 + 784
     sizes = [5000, 3, 4097]
     with dry(d=sum(sizes), tensor_numel=sizes, stride=9112, bucket_bytes=20480) as ctx:
         padded, chunks, buckets = ctx.get_plan()
-        assert padded == 5000 + 4 + 4100 and chunks == 2 + 1 + 2 and buckets == 2
+        assert padded == 5000 + 4 + 4100 and chunks == 5 + 1 + 5 and buckets == 2
 
 
 def test_null_context_is_an_error_not_a_crash():
