@@ -22,9 +22,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 STEP_BYTES = 24                 # local step: read x, v, h, c; write x, v (fp32)
-# HBM bytes per launch of the step kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by a copy kernel of known size; None until measured (see profiles/).
-STEP_TRAFFIC_BYTES = None
+# HBM bytes per launch of the step kernel at this workload from two rocprofv3 --pmc runs
+# (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999, factors from the known-size copy kernel):
+# profiles/kernels_C2_W16_d11.2M_hbm_counters.md
+STEP_TRAFFIC_BYTES = 4.3038e9
 
 
 def round_bytes(W, d, k):
