@@ -6,9 +6,12 @@ mean on the averaging stream, take k local momentum-SGD steps on the compute str
 line 6.  Workload: the ResNet18-sized flat vector (W=16, d=11.2M fp32, momentum 0.9, weight decay
 5e-4, lr 0.05, noise 0.01), all state resident in HBM before timing starts; synthetic data.
 
-Prints ONE JSON line.  `value` = worker-param-updates/s = W*d*k / round time at k=2; the k sweep,
-the other schedules, the roofline of the dominant kernel (the fused local step) and the CPU oracle
-timed on the host cores ride along in the same line.
+Two ways of running the same round are timed:
+  separate    cocod_average_begin; cocod_local_steps(k); cocod_average_end_apply
+  fused_tail  cocod_average_begin; cocod_local_steps_end_apply(k)   (line 6 inside the last step)
+Prints ONE JSON line.  `value` = worker-param-updates/s = W*d*k / round time at k=2 for the variant
+named in config.variant; the other variant, the k sweep, the serial schedules, the roofline of the
+step kernels and the CPU oracle timed on the host cores ride along in the same line.
 """
 import argparse
 import json
@@ -21,40 +24,60 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
-STEP_BYTES = 24                 # local step: read x, v, h, c; write x, v (fp32)
-# HBM bytes per launch of the step kernel at this workload from two rocprofv3 --pmc runs
+STEP_BYTES = 24                 # plain local step: read x, v, h, c; write x, v (fp32)
+# HBM bytes per launch of the plain step kernel at this workload from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999, factors from the known-size copy kernel):
 # profiles/kernels_C2_W16_d11.2M_hbm_counters.md
 STEP_TRAFFIC_BYTES = 4.3038e9
 
 
-def round_bytes(W, d, k):
-    """Algorithmic HBM bytes of one round: k steps, mean (read W rows, write 1), line 6 (read x, snap, mean once; write x)."""
-    return W * d * (STEP_BYTES * k + 4 * (1 + 1 / W) + 12 + 4 / W)
+def model_round_bytes(W, d, k):
+    """Bytes of one round in the accounting where line 6 is a pass of its own:
+    k steps (24) + mean (4(1+1/W)) + line 6 with the mean read once per column (12+4/W)."""
+    return W * d * (STEP_BYTES * k + 16 + 8 / W)
 
 
-def time_rounds(ctx, torch, k, rounds, warmup, want_step_times):
-    """Seconds per round over `rounds` timed rounds, and the average step-kernel duration in seconds
-    measured over the same rounds (the kernel's own start/stop timestamps on the compute stream)."""
+def tail_step_bytes(W, d, k):
+    """Step that carries line 6: the plain step's 24 B plus the stored model (not at k=1, where the
+    step reads it anyway) plus the mean, shared by the W workers of a column."""
+    return W * d * (STEP_BYTES + (4 if k > 1 else 0) + 4 / W)
+
+
+def moved_round_bytes(W, d, k, variant):
+    if variant == "separate":
+        return model_round_bytes(W, d, k)
+    return W * d * (STEP_BYTES * (k - 1) + 4 * (1 + 1 / W)) + tail_step_bytes(W, d, k)
+
+
+def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
+    """Seconds per round over `rounds` timed rounds and, measured over the same rounds from the
+    kernels' own start/stop timestamps on the compute stream, the average duration in seconds of the
+    plain step kernel and of the step kernel that carries line 6 (None where there was no launch)."""
+    def one_round():
+        ctx.average_begin()
+        if variant == "separate":
+            ctx.local_steps(k)
+            ctx.average_end_apply()
+        else:
+            ctx.local_steps_end_apply(k)
     for _ in range(warmup):
-        ctx.round(k)
+        one_round()
     ctx.sync()
     ctx.step_timing(rounds * k if want_step_times else 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(rounds):
-        ctx.average_begin()
-        ctx.local_steps(k)
-        ctx.average_end_apply()
+        one_round()
     ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    step_s = None
+    avg = [None, None]
     if want_step_times:
-        total_ms, n = ctx.step_timing_read()
-        step_s = total_ms / max(n, 1) / 1e3
+        for i, (total_ms, n) in enumerate(ctx.step_timing_read()):
+            if n:
+                avg[i] = total_ms / n / 1e3
         ctx.step_timing(0)
-    return elapsed / rounds, step_s
+    return elapsed / rounds, avg[0], avg[1]
 
 
 def cpu_baseline(cfg, k):
@@ -74,8 +97,14 @@ def cpu_baseline(cfg, k):
     per_round = (time.perf_counter() - t0) / rounds
     return {"value": W * d * k / per_round, "unit": "worker-param-updates/s", "cores": orc.num_threads(),
             "kind": "oracle", "ms_per_round": per_round * 1e3,
-            "algorithmic_GBps_fp32_equiv": round_bytes(W, d, k) / per_round / 1e9,
             "sample": "full shape W=%d d=%d k=%d, %d rounds after 1 untimed, fp64 C oracle with OpenMP" % (W, d, k, rounds)}
+
+
+def roofline(name, algorithmic_bytes, seconds, launches, traffic):
+    achieved = algorithmic_bytes / seconds / 1e9
+    return {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_launch_ms": seconds * 1e3,
+            "launches_timed": launches, "algorithmic_bytes_per_launch": algorithmic_bytes}
 
 
 def main():
@@ -84,8 +113,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50, help="timed rounds")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--k", type=int, default=2, help="local steps per round for the headline value")
+    ap.add_argument("--variant", choices=("separate", "fused_tail"), default="fused_tail")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--headline-only", action="store_true", help="skip the k sweep and the other schedules")
+    ap.add_argument("--headline-only", action="store_true", help="skip the other variant, the k sweep and the serial schedules")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the W workers are replicas in one MI355X's HBM); "
@@ -120,9 +150,8 @@ def main():
     ctx.fill_quadratic()
     ctx.sync()
 
-    k = args.k
-    per_round, avg_step_s = time_rounds(ctx, torch, k, args.steps, args.warmup, True)
-    achieved = STEP_BYTES * W * d / avg_step_s / 1e9
+    k, variant = args.k, args.variant
+    per_round, plain_s, tail_s = time_rounds(ctx, torch, k, args.steps, args.warmup, variant)
     out = {
         "metric": "worker-param-updates/s per CoCoD round (W=16, d=11.2M)",
         "value": W * d * k / per_round,
@@ -132,29 +161,38 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C2 ResNet18-sized flat vector: W=16 workers x d=11.2M fp32, quadratic+Philox-noise "
-                               "gradient, momentum 0.9, wd 5e-4, lr 0.05", "k": k, "schedule": "overlap (2 streams)",
-                   "W": W, "d": d},
-        "round_algorithmic_GBps": round_bytes(W, d, k) / per_round / 1e9,
-        "round_frac_of_hbm_peak": round_bytes(W, d, k) / per_round / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "quad_step_kernel<momentum, noise>", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": STEP_TRAFFIC_BYTES, "avg_launch_ms": avg_step_s * 1e3,
-                     "launches_timed": args.steps * k, "algorithmic_bytes_per_launch": STEP_BYTES * W * d},
+                               "gradient, momentum 0.9, wd 5e-4, lr 0.05", "k": k, "variant": variant,
+                   "schedule": "overlap (2 streams)", "W": W, "d": d},
+        "round_model_GBps": model_round_bytes(W, d, k) / per_round / 1e9,
+        "round_moved_GBps": moved_round_bytes(W, d, k, variant) / per_round / 1e9,
+        "round_moved_frac_of_hbm_peak": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / HBM_PEAK_GBS,
     }
+    if plain_s:
+        n_plain = args.steps * (k if variant == "separate" else k - 1)
+        out["roofline"] = roofline("quad_step_kernel<momentum, noise, plain>", STEP_BYTES * W * d, plain_s, n_plain,
+                                   STEP_TRAFFIC_BYTES)
+    if tail_s:
+        tail = roofline("quad_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k), tail_s, args.steps, None)
+        out["roofline_tail" if plain_s else "roofline"] = tail
     if not args.headline_only:
-        sweep = {}
-        for kk in cfg["k"]:
-            pr, sm = time_rounds(ctx, torch, kk, args.steps, 2, True)
-            sweep["k=%d" % kk] = {"ms_per_round": pr * 1e3, "updates_per_s": W * d * kk / pr,
-                                  "round_GBps": round_bytes(W, d, kk) / pr / 1e9,
-                                  "step_kernel_ms": sm * 1e3}
-        out["k_sweep"] = sweep
+        variants = {}
+        for name in ("separate", "fused_tail"):
+            sweep = {}
+            for kk in cfg["k"]:
+                pr, ps, ts = time_rounds(ctx, torch, kk, args.steps, 2, name)
+                sweep["k=%d" % kk] = {"ms_per_round": pr * 1e3, "updates_per_s": W * d * kk / pr,
+                                      "model_GBps": model_round_bytes(W, d, kk) / pr / 1e9,
+                                      "moved_GBps": moved_round_bytes(W, d, kk, name) / pr / 1e9,
+                                      "plain_step_ms": ps * 1e3 if ps else None,
+                                      "tail_step_ms": ts * 1e3 if ts else None}
+            variants[name] = sweep
+        out["k_sweep"] = variants
         sched = {}
-        for name, code in (("serial", P.SCHED_SERIAL), ("fused", P.SCHED_FUSED), ("overlap", P.SCHED_OVERLAP)):
+        for name, code in (("serial", P.SCHED_SERIAL), ("serial_fused_mean_line6", P.SCHED_FUSED), ("overlap", P.SCHED_OVERLAP)):
             ctx.set_schedule(code)
-            pr, _ = time_rounds(ctx, torch, k, args.steps, 2, False)
+            pr, _, _ = time_rounds(ctx, torch, k, args.steps, 2, "separate", False)
             sched[name] = pr * 1e3
-        out["schedule_ms_per_round"] = sched
+        out["separate_schedule_ms_per_round"] = sched
     ctx.close()
     del xA, xB, v, mean, h, c
     torch.cuda.empty_cache()

@@ -157,6 +157,18 @@ int cocod_average_begin(cocod_ctx *ctx);
  */
 int cocod_average_end_apply(cocod_ctx *ctx);
 
+/*
+ * Step II and line 6 together: k local steps of which the LAST one applies line 6 to the model it
+ * has just computed, before storing it (x = x^_t + ((x - gamma v) - x_t^i) in the step kernel's
+ * registers), and closes the round.  Same arithmetic, in the same order, as
+ * cocod_local_steps(k) followed by cocod_average_end_apply, but the separate pass of line 6 over
+ * the models (read x, read x_t, write x) disappears: 8 bytes per parameter less per round (24 at
+ * k = 1, where the step reads the stored models anyway).  The join moves in front of the last
+ * step, so the mean overlaps the first k-1 steps only.  k = 0 is cocod_average_end_apply.
+ * AVERAGING -> IDLE; COCOD_ERR_STATE if no round is open.
+ */
+int cocod_local_steps_end_apply(cocod_ctx *ctx, int k);
+
 /* Choose how Step I is scheduled; only legal while IDLE.  Default COCOD_SCHED_OVERLAP. */
 int cocod_set_schedule(cocod_ctx *ctx, int schedule);
 
@@ -182,9 +194,11 @@ int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks,
  * launches carry the runtime's own start/stop timestamps (events on compute_stream, owned by the
  * context); n = 0 switches it off.  cocod_step_timing_read waits for compute_stream, returns the
  * summed kernel durations and the number of launches measured since the last read, and rearms.
+ * Index 0 of both arrays: plain local steps; index 1: steps that carry line 6
+ * (cocod_local_steps_end_apply's last step).
  */
 int cocod_step_timing(cocod_ctx *ctx, int max_launches);
-int cocod_step_timing_read(cocod_ctx *ctx, double *total_ms, uint32_t *launches);
+int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches[2]);
 
 /* Block the host until both streams have drained. */
 int cocod_sync(cocod_ctx *ctx);

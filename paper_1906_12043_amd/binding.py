@@ -62,6 +62,7 @@ def lib():
             "cocod_destroy": ([vp], i32),
             "cocod_sync": ([vp], i32),
             "cocod_local_steps": ([vp, i32], i32),
+            "cocod_local_steps_end_apply": ([vp, i32], i32),
             "cocod_average_begin": ([vp], i32),
             "cocod_average_end_apply": ([vp], i32),
             "cocod_set_schedule": ([vp, i32], i32),
@@ -200,6 +201,14 @@ class Context:
     def average_end_apply(self):
         return cocod_average_end_apply(self.handle)
 
+    def local_steps_end_apply(self, k):
+        return _check(lib().cocod_local_steps_end_apply(self.handle, k), self.handle)
+
+    def round_fused_tail(self, k):
+        """One round with line 6 applied inside the last local step."""
+        self.average_begin()
+        self.local_steps_end_apply(k)
+
     def round(self, k):
         """One pass of the while-loop body of Algorithm 1."""
         self.average_begin()
@@ -240,10 +249,10 @@ class Context:
         return _check(lib().cocod_step_timing(self.handle, max_launches), self.handle)
 
     def step_timing_read(self):
-        """(summed step-kernel milliseconds, launches measured) since the last read."""
-        total, n = C.c_double(), C.c_uint32()
-        _check(lib().cocod_step_timing_read(self.handle, C.byref(total), C.byref(n)), self.handle)
-        return total.value, n.value
+        """[(summed kernel milliseconds, launches)] for plain steps and for steps carrying line 6."""
+        total, n = (C.c_double * 2)(), (C.c_uint32 * 2)()
+        _check(lib().cocod_step_timing_read(self.handle, total, n), self.handle)
+        return [(total[0], n[0]), (total[1], n[1])]
 
     def fill_quadratic(self):
         return _check(lib().cocod_fill_quadratic(self.handle), self.handle)

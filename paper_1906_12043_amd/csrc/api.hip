@@ -35,6 +35,7 @@ struct cocod_ctx {
     bool dry = false;
     bool timing = false;                // bracket step launches with start/stop events
     std::vector<hipEvent_t> t_start, t_stop;   // event pool for step timing (owned)
+    std::vector<char> t_kind;           // per timed launch: 0 plain step, 1 step with line 6
     size_t t_used = 0;
     std::string err;
 };
@@ -288,49 +289,88 @@ int cocod_sync(cocod_ctx *ctx)
     return COCOD_OK;
 }
 
-int cocod_local_steps(cocod_ctx *ctx, int k)
+// One local step on the compute stream; with_line6 fuses line 6 into it (last step of a round).
+static int enqueue_step(cocod_ctx *ctx, bool with_line6)
 {
-    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    // Keep the stored models intact: the first step of an open round reads them and
+    // writes the spare buffer, which then becomes the live one.
+    float *dst = ctx->store_pending ? ctx->spare : ctx->live;
+    if (!ctx->dry) {
+        cocod::StepParams p{};
+        p.table = ctx->d_chunks;
+        p.n_chunks = static_cast<uint32_t>(ctx->chunks.size());
+        p.W = ctx->cfg.W;
+        p.stride = ctx->cfg.stride;
+        p.x_in = ctx->live;
+        p.x_out = dst;
+        p.v = ctx->cfg.v;
+        p.h = ctx->cfg.h;
+        p.c = ctx->cfg.c;
+        p.snap = with_line6 ? ctx->snap : nullptr;
+        p.mean = ctx->cfg.mean;
+        p.lr = ctx->cfg.lr;
+        p.momentum = ctx->cfg.momentum;
+        p.weight_decay = ctx->cfg.weight_decay;
+        p.sigma = ctx->cfg.noise_sigma;
+        p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
+        p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
+        p.step = static_cast<uint32_t>(ctx->step);
+        hipEvent_t t0 = nullptr, t1 = nullptr;
+        if (ctx->timing && ctx->t_used < ctx->t_start.size()) {
+            t0 = ctx->t_start[ctx->t_used];
+            t1 = ctx->t_stop[ctx->t_used];
+            ctx->t_kind[ctx->t_used] = with_line6 ? 1 : 0;
+            ctx->t_used += 1;
+        }
+        COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p, t0, t1));
+    }
+    if (ctx->store_pending) {
+        ctx->spare = ctx->live;
+        ctx->live = dst;
+        ctx->store_pending = false;
+    }
+    ctx->step += 1;
+    return COCOD_OK;
+}
+
+static int check_steps(cocod_ctx *ctx, int k)
+{
     if (k < 0) return fail(ctx, COCOD_ERR_INVALID, "k must be >= 0, got %d", k);
     if (ctx->step + static_cast<uint64_t>(k) > 0xffffffffull)
         return fail(ctx, COCOD_ERR_INVALID, "step counter would exceed 2^32 - 1");
-    for (int s = 0; s < k; ++s) {
-        // Keep the stored models intact: the first step of an open round reads them and
-        // writes the spare buffer, which then becomes the live one.
-        float *dst = ctx->store_pending ? ctx->spare : ctx->live;
-        if (!ctx->dry) {
-            cocod::StepParams p{};
-            p.table = ctx->d_chunks;
-            p.n_chunks = static_cast<uint32_t>(ctx->chunks.size());
-            p.W = ctx->cfg.W;
-            p.stride = ctx->cfg.stride;
-            p.x_in = ctx->live;
-            p.x_out = dst;
-            p.v = ctx->cfg.v;
-            p.h = ctx->cfg.h;
-            p.c = ctx->cfg.c;
-            p.lr = ctx->cfg.lr;
-            p.momentum = ctx->cfg.momentum;
-            p.weight_decay = ctx->cfg.weight_decay;
-            p.sigma = ctx->cfg.noise_sigma;
-            p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
-            p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
-            p.step = static_cast<uint32_t>(ctx->step);
-            hipEvent_t t0 = nullptr, t1 = nullptr;
-            if (ctx->timing && ctx->t_used < ctx->t_start.size()) {
-                t0 = ctx->t_start[ctx->t_used];
-                t1 = ctx->t_stop[ctx->t_used];
-                ctx->t_used += 1;
-            }
-            COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p, t0, t1));
+    return COCOD_OK;
+}
+
+int cocod_local_steps(cocod_ctx *ctx, int k)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    int rc = check_steps(ctx, k);
+    for (int s = 0; s < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
+    return rc;
+}
+
+int cocod_local_steps_end_apply(cocod_ctx *ctx, int k)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (!ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_local_steps_end_apply: no round is open");
+    int rc = check_steps(ctx, k);
+    if (rc != COCOD_OK) return rc;
+    if (k == 0) return cocod_average_end_apply(ctx);
+    for (int s = 0; s + 1 < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
+    if (rc != COCOD_OK) return rc;
+    if (!ctx->dry) {
+        // the mean must be complete before the last step starts: it is consumed inside it
+        if (ctx->schedule != COCOD_SCHED_OVERLAP) {
+            rc = enqueue_mean(ctx, ctx->s_compute);
+            if (rc != COCOD_OK) return rc;
+        } else if (ctx->s_avg != ctx->s_compute) {
+            COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
         }
-        if (ctx->store_pending) {
-            ctx->spare = ctx->live;
-            ctx->live = dst;
-            ctx->store_pending = false;
-        }
-        ctx->step += 1;
     }
+    rc = enqueue_step(ctx, true);
+    if (rc != COCOD_OK) return rc;
+    ctx->averaging = false;
+    ctx->snap = nullptr;
     return COCOD_OK;
 }
 
@@ -451,22 +491,24 @@ int cocod_step_timing(cocod_ctx *ctx, int max_launches)
         ctx->t_start.push_back(a);
         COCOD_HIP(ctx, hipEventCreate(&b));
         ctx->t_stop.push_back(b);
+        ctx->t_kind.push_back(0);
     }
     return COCOD_OK;
 }
 
-int cocod_step_timing_read(cocod_ctx *ctx, double *total_ms, uint32_t *launches)
+int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches[2])
 {
     if (!ctx || !total_ms || !launches) return fail(nullptr, COCOD_ERR_INVALID, "ctx, total_ms and launches must not be NULL");
-    *total_ms = 0.0;
-    *launches = 0;
+    total_ms[0] = total_ms[1] = 0.0;
+    launches[0] = launches[1] = 0;
     if (ctx->dry) return COCOD_OK;
     COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
     for (size_t i = 0; i < ctx->t_used && i < ctx->t_stop.size(); ++i) {
         float ms = 0.0f;
         COCOD_HIP(ctx, hipEventElapsedTime(&ms, ctx->t_start[i], ctx->t_stop[i]));
-        *total_ms += ms;
-        *launches += 1;
+        const int kind = ctx->t_kind[i] ? 1 : 0;
+        total_ms[kind] += ms;
+        launches[kind] += 1;
     }
     ctx->t_used = 0;
     return COCOD_OK;

@@ -111,7 +111,10 @@ __global__ __launch_bounds__(kAvgThreads) void correct_kernel(float *x, const fl
     correct_column(x + e, snap + e, ld4(mean + e), stride, W);
 }
 
-template <bool WEIGHTED>
+// WREG > 0: W <= WREG and the column's stored models stay in registers between the two passes, so
+// each is read from memory once (12 + 4/W bytes per parameter).  WREG == 0: any W, the stored models
+// are read a second time for line 6.
+template <bool WEIGHTED, int WREG>
 __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, const float *snap, uint64_t stride,
                                                                    uint32_t W, uint64_t begin, uint64_t n_quads,
                                                                    const float *weights, float *mean)
@@ -119,10 +122,39 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
     const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
     if (quad >= n_quads) return;
     const uint64_t e = begin + quad * 4;
-    const float4 m = column_mean<WEIGHTED>(snap + e, stride, W, weights);
+    if (WREG == 0) {
+        const float4 m = column_mean<WEIGHTED>(snap + e, stride, W, weights);
+        st4(mean + e, m);
+        correct_column(x + e, snap + e, m, stride, W);
+        return;
+    }
+    constexpr int R = WREG > 0 ? WREG : 1;
+    float4 s[R];
+    #pragma unroll
+    for (int i = 0; i < R; ++i)
+        if (static_cast<uint32_t>(i) < W) s[i] = ld4_stream(snap + e + static_cast<uint64_t>(i) * stride);
+    float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+    #pragma unroll
+    for (int i = 0; i < R; ++i) {                          // same order and operations as column_mean
+        if (static_cast<uint32_t>(i) >= W) break;
+        const float pw = WEIGHTED ? weights[i] : 1.0f;
+        m.x += pw * s[i].x; m.y += pw * s[i].y; m.z += pw * s[i].z; m.w += pw * s[i].w;
+    }
+    if (!WEIGHTED) {
+        const float inv = 1.0f / static_cast<float>(W);
+        m.x *= inv; m.y *= inv; m.z *= inv; m.w *= inv;
+    }
     st4(mean + e, m);
-    // the stored models are read a second time here; they were just touched, so this pass hits cache
-    correct_column(x + e, snap + e, m, stride, W);
+    #pragma unroll
+    for (int i = 0; i < R; ++i) {
+        if (static_cast<uint32_t>(i) >= W) break;
+        float *xp = x + e + static_cast<uint64_t>(i) * stride;
+        const float4 xr = ld4_stream(xp);
+        float4 o;
+        o.x = m.x + (xr.x - s[i].x); o.y = m.y + (xr.y - s[i].y);
+        o.z = m.z + (xr.z - s[i].z); o.w = m.w + (xr.w - s[i].w);
+        st4_stream(xp, o);
+    }
 }
 
 inline uint32_t blocks_for(uint64_t n_quads) { return static_cast<uint32_t>((n_quads + kAvgThreads - 1) / kAvgThreads); }
@@ -156,8 +188,18 @@ hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, 
     const uint64_t n_quads = (end - begin) / 4;
     if (n_quads == 0) return hipSuccess;
     const dim3 grid(blocks_for(n_quads)), block(kAvgThreads);
-    if (weights) hipLaunchKernelGGL((mean_correct_kernel<true>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
-    else         hipLaunchKernelGGL((mean_correct_kernel<false>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+    if (W <= 8) {
+        if (weights) hipLaunchKernelGGL((mean_correct_kernel<true, 8>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+        else         hipLaunchKernelGGL((mean_correct_kernel<false, 8>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+        return hipGetLastError();
+    }
+    if (W <= 16) {
+        if (weights) hipLaunchKernelGGL((mean_correct_kernel<true, 16>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+        else         hipLaunchKernelGGL((mean_correct_kernel<false, 16>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+        return hipGetLastError();
+    }
+    if (weights) hipLaunchKernelGGL((mean_correct_kernel<true, 0>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+    else         hipLaunchKernelGGL((mean_correct_kernel<false, 0>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
     return hipGetLastError();
 }
 

@@ -30,6 +30,8 @@ struct StepParams {
     float *v;            // momentum, unused when momentum == 0
     const float *h;
     const float *c;
+    const float *snap;   // non-null: this is the last step of a round and line 6 is applied to its result
+    const float *mean;   //           x = mean + (x_new - snap); mean is [stride], valid when snap is set
     float lr, momentum, weight_decay, sigma;
     uint32_t key0, key1; // generator key (seed low, seed high)
     uint32_t step;       // global step counter t

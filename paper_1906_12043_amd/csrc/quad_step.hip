@@ -61,12 +61,16 @@ __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const S
     return f4{a.z[3], b.z[0], b.z[1], b.z[2]};
 }
 
-template <bool HAS_V, bool NOISE>
+// TAIL: 0 = plain local step; 1 = last step of a round with line 6 applied to the fresh model
+// before it is stored, x = mean + ((x - gamma v) - snap); 2 = the same when the step reads the
+// stored models themselves (k = 1: snap is x_in, no extra read).
+template <bool HAS_V, bool NOISE, int TAIL>
 __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParams p)
 {
     const Chunk ck = p.table[blockIdx.x];
     const uint32_t worker = blockIdx.y;
-    const uint64_t row = static_cast<uint64_t>(worker) * p.stride + static_cast<uint64_t>(ck.mem_quad) * 4;
+    const uint64_t col = static_cast<uint64_t>(ck.mem_quad) * 4;
+    const uint64_t row = static_cast<uint64_t>(worker) * p.stride + col;
     const uint32_t bytes = ((ck.n + 3u) & ~3u) * 4u;      // whole quads: a tensor's tail quad ends in pads
     const __amdgpu_buffer_rsrc_t rx_in = make_rsrc(p.x_in + row, bytes);
     const __amdgpu_buffer_rsrc_t rx_out = make_rsrc(p.x_out + row, bytes);
@@ -80,6 +84,13 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     const f4 v0 = HAS_V ? load_quad(rv, off) : f4{0.f, 0.f, 0.f, 0.f};
     const f4 h = load_quad(rh, off);
     const f4 c = load_quad(rc, off);
+    f4 snap = x0, mean = f4{0.f, 0.f, 0.f, 0.f};
+    if (TAIL == 1) snap = load_quad(make_rsrc(p.snap + row, bytes), off);
+    if (TAIL != 0) {
+        // the mean is shared by the W workers of a column: ordinary cached load
+        const __amdgpu_buffer_rsrc_t rm = make_rsrc(p.mean + col, bytes);
+        mean = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rm, static_cast<int>(off), 0, 0));
+    }
 
     f4 g = h * (x0 - c);
     if (NOISE)
@@ -88,6 +99,7 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     f4 v = v0;
     if (HAS_V) { v = p.momentum * v0 + g; g = v; }
     f4 x = x0 - p.lr * g;
+    if (TAIL != 0) x = mean + (x - snap);
 
     if (e + 4 > ck.n && e < ck.n) {                       // tensor tail: alignment pads keep their old values
         const uint32_t keep = ck.n - e;                   // 1..3 real elements
@@ -99,17 +111,25 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     if (HAS_V) store_quad(rv, off, v);
 }
 
-}  // namespace
-
-hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
+template <int TAIL>
+void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
     const dim3 grid(p.n_chunks, p.W), block(kStepThreads);
     const bool has_v = p.momentum != 0.0f, noise = p.sigma != 0.0f;
     // start/stop (may be null) receive the kernel's own begin and end timestamps
-    if (has_v && noise)       hipExtLaunchKernelGGL((quad_step_kernel<true, true>), grid, block, 0, stream, start, stop, 0, p);
-    else if (has_v && !noise) hipExtLaunchKernelGGL((quad_step_kernel<true, false>), grid, block, 0, stream, start, stop, 0, p);
-    else if (noise)           hipExtLaunchKernelGGL((quad_step_kernel<false, true>), grid, block, 0, stream, start, stop, 0, p);
-    else                      hipExtLaunchKernelGGL((quad_step_kernel<false, false>), grid, block, 0, stream, start, stop, 0, p);
+    if (has_v && noise)       hipExtLaunchKernelGGL((quad_step_kernel<true, true, TAIL>), grid, block, 0, stream, start, stop, 0, p);
+    else if (has_v && !noise) hipExtLaunchKernelGGL((quad_step_kernel<true, false, TAIL>), grid, block, 0, stream, start, stop, 0, p);
+    else if (noise)           hipExtLaunchKernelGGL((quad_step_kernel<false, true, TAIL>), grid, block, 0, stream, start, stop, 0, p);
+    else                      hipExtLaunchKernelGGL((quad_step_kernel<false, false, TAIL>), grid, block, 0, stream, start, stop, 0, p);
+}
+
+}  // namespace
+
+hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
+{
+    if (!p.snap)                 launch_tail<0>(stream, p, start, stop);
+    else if (p.snap != p.x_in)   launch_tail<1>(stream, p, start, stop);
+    else                         launch_tail<2>(stream, p, start, stop);
     return hipGetLastError();
 }
 

@@ -189,3 +189,23 @@ def test_null_context_is_an_error_not_a_crash():
     assert L.cocod_sync(None) == P.ERR_INVALID
     assert L.cocod_destroy(None) == P.OK
     assert L.cocod_last_error(None) is not None
+
+
+def test_local_steps_end_apply_state_machine():
+    with dry() as ctx:
+        with pytest.raises(P.CocodError) as e:
+            ctx.local_steps_end_apply(2)
+        assert e.value.status == P.ERR_STATE
+        a = ctx.live_model()
+        ctx.average_begin()
+        ctx.local_steps_end_apply(3)
+        assert not ctx.is_averaging() and ctx.get_step() == 3 and ctx.live_model() != a
+        ctx.average_begin()
+        ctx.local_steps_end_apply(0)
+        assert not ctx.is_averaging() and ctx.get_step() == 3
+        ctx.average_begin()
+        with pytest.raises(P.CocodError) as e:
+            ctx.local_steps_end_apply(-1)
+        assert e.value.status == P.ERR_INVALID and ctx.is_averaging()
+        ctx.local_steps_end_apply(1)
+        assert not ctx.is_averaging() and ctx.get_step() == 4

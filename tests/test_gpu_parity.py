@@ -193,3 +193,31 @@ def test_checkpoint_resume_is_bit_identical():
     r.ctx.round(k); r.ctx.round(k)
     assert torch.equal(r.x_raw()[:, :d], want)
     a.close(); r.close()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+@pytest.mark.parametrize("packed", [False, True])
+def test_line6_inside_last_step_is_bit_identical_to_separate_kernels(k, packed):
+    W, rounds = 5, 4
+    sizes = [5, 4096, 1, 3, 8191, 64, 4097, 2, 10000, 7] if packed else None
+    d = sum(sizes) if packed else 50_003
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=31)
+    h, c = synth_inputs.quadratic_data(12, W, d)
+    a = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
+    b = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    for r in range(rounds):
+        a.ctx.round(k)
+        b.ctx.round_fused_tail(k)
+        o.round(k)
+        assert not b.ctx.is_averaging() and b.ctx.get_step() == a.ctx.get_step()
+    assert np.array_equal(a.x(), b.x()) and np.array_equal(a.vel(), b.vel())
+    check_state(b, o, what="fused tail k=%d" % k)
+    for sched in (P.SCHED_SERIAL, P.SCHED_FUSED):           # mean taken on the compute stream just before the last step
+        b.ctx.set_schedule(sched)
+        a.ctx.round(k); b.ctx.round_fused_tail(k)
+        assert np.array_equal(a.x(), b.x())
+    b.ctx.average_begin(); b.ctx.local_steps_end_apply(0)    # k = 0: plain line 6
+    a.ctx.average_begin(); a.ctx.average_end_apply()
+    assert np.array_equal(a.x(), b.x())
+    a.close(); b.close()
