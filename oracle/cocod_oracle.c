@@ -102,6 +102,7 @@ void oracle_normal_quad(uint64_t seed, uint32_t tag, uint32_t worker, uint32_t s
 void oracle_normals(uint64_t seed, uint32_t tag, uint32_t worker, uint32_t step,
                     uint64_t j0, uint64_t n, double *out)
 {
+    #pragma omp parallel for schedule(static) if (n > 4096)
     for (uint64_t m = 0; m < n; ++m) {
         uint64_t j = j0 + m;
         double z[4];
