@@ -107,8 +107,57 @@ def roofline(name, algorithmic_bytes, seconds, launches, traffic):
             "launches_timed": launches, "algorithmic_bytes_per_launch": algorithmic_bytes}
 
 
+MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X published dense fp32 matrix rate
+
+
+def bench_mlp(args):
+    """C4: W=16 perceptron workers 3072-1024-10, batch 128, k=2: rounds/s, and the MFMA roofline of a
+    local step (the two big contractions are 2 * 2*B*in*hid flops per worker-step)."""
+    import torch
+    import paper_1906_12043_amd as P
+    import synth_inputs
+    cfg = synth_inputs.CONFIGS["C4_mlp"]
+    W, shape, batch, k = cfg["W"], cfg["mlp"], cfg["batch"], args.k
+    d = synth_inputs.mlp_param_count(*shape)
+    dev = torch.device("cuda:0")
+    stride, _, _ = P.plan_layout(d)
+    xA = torch.zeros((W, stride), device=dev)
+    xA[:, :d] = torch.from_numpy(synth_inputs.mlp_he_init(cfg["seed"], *shape)).to(dev)
+    xB, v = torch.zeros((W, stride), device=dev), torch.zeros((W, stride), device=dev)
+    mean = torch.zeros(stride, device=dev)
+    s_compute, s_avg = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+    ctx = P.Context(W=W, d=d, stride=stride, xA=xA, xB=xB, v=v, mean=mean, grad=P.GRAD_MLP, mlp=(*shape, batch),
+                    lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"],
+                    compute_stream=s_compute, avg_stream=s_avg)
+    per_round, step_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "separate")
+    n_in, n_hid, n_out = shape
+    gemm_flops = W * 2 * (2 * batch * n_in * n_hid)
+    all_flops = gemm_flops + W * 3 * (2 * batch * n_hid * n_out)
+    achieved = gemm_flops / step_s / 1e12
+    out = {
+        "metric": "worker-param-updates/s per CoCoD round, MLP-gradient workers (W=16, d=3.16M)",
+        "value": W * d * k / per_round, "unit": "worker-param-updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": per_round * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C4 MLP workers 3072-1024-10, batch 128 fresh N(0,1) inputs per worker-step, momentum 0.9, "
+                               "lr 0.05", "k": k, "W": W, "d": d, "variant": "separate"},
+        "local_step_ms": step_s * 1e3,
+        "local_step_TFLOPs_all": all_flops / step_s / 1e12,
+        "roofline": {"bound": "mfma", "kernel": "one local step (6 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
+                     "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": step_s * 1e3,
+                     "launches_timed": args.steps * k, "algorithmic_flops_per_launch": gemm_flops},
+    }
+    ctx.close()
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", choices=("C2", "C4"), default="C2",
+                    help="C2: the headline quadratic workload; C4: the MLP-gradient workers")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50, help="timed rounds")
     ap.add_argument("--warmup", type=int, default=5)
@@ -131,6 +180,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.workload == "C4":
+        return bench_mlp(args)
 
     cfg = synth_inputs.CONFIGS["C2_resnet18"]
     W, d = cfg["W"], cfg["d"]

@@ -212,6 +212,17 @@ int cocod_sync(cocod_ctx *ctx);
 int cocod_fill_quadratic(cocod_ctx *ctx);
 
 /*
+ * Inspection of the MLP kind's work space after a local step (device pointers owned by the
+ * context, valid until cocod_destroy; any output pointer may be NULL):
+ *   X [W][batch][mlp_in] last mini-batch, H [W][batch][mlp_hidden] relu output,
+ *   dA [W][batch][mlp_hidden] gradient at the hidden pre-activation,
+ *   dZ [W][batch][*dz_pitch] gradient at the logits (first mlp_out entries of each row),
+ *   y [W][batch] labels.
+ */
+int cocod_mlp_workspace(const cocod_ctx *ctx, float **X, float **H, float **dA, float **dZ, int32_t **y,
+                        uint32_t *dz_pitch);
+
+/*
  * Generator check: n standard normals of stream `tag` for (worker, step) at flat
  * indices j0 .. j0+n-1, written to device memory `out` on `stream`, produced by the
  * same device routine as the local step's noise (fast = 1) or by the accurate routine

@@ -38,8 +38,12 @@ def minibatch(seed, worker, step, batch, n_in, n_out):
     return X.reshape(batch, n_in), y
 
 
-def loss_and_gradient(theta, X, y, n_in, n_hidden, n_out):
-    """Mean softmax cross-entropy of the perceptron and its gradient w.r.t. the flat parameters."""
+def loss_and_gradient(theta, X, y, n_in, n_hidden, n_out, margin=None):
+    """Mean softmax cross-entropy of the perceptron and its gradient w.r.t. the flat parameters.
+
+    With margin set, also returns the hidden units n for which some sample's pre-activation has
+    |A[b][n]| < margin: there the relu decision A > 0 depends on rounding, and an fp32 evaluation
+    may legitimately take the other branch (which changes column n of dW1 and db1[n] only)."""
     W1, b1, W2, b2 = split(theta, n_in, n_hidden, n_out)
     B = X.shape[0]
     A = X @ W1 + b1
@@ -58,7 +62,10 @@ def loss_and_gradient(theta, X, y, n_in, n_hidden, n_out):
     dA = dH * (A > 0.0)
     dW1 = X.T @ dA
     db1 = dA.sum(axis=0)
-    return loss, np.concatenate([dW1.ravel(), db1, dW2.ravel(), db2])
+    grad = np.concatenate([dW1.ravel(), db1, dW2.ravel(), db2])
+    if margin is None:
+        return loss, grad
+    return loss, grad, np.unique(np.nonzero(np.abs(A) < margin)[1])
 
 
 class MlpOracle:
@@ -81,17 +88,35 @@ class MlpOracle:
         self.step = 0
         self.averaging = False
         self.last_loss = np.zeros(W)
+        # see loss_and_gradient; an fp32 dot product of length 3072 with O(1) terms is good to a few 1e-6
+        self.margin = 2e-5
+        self.ambiguous = [set() for _ in range(W)]         # per worker: hidden units with a borderline relu
 
     def local_steps(self, k):
         n_in, n_hidden, n_out = self.shape
         for _ in range(k):
             for i in range(self.W):
                 X, y = minibatch(self.seed, i, self.step, self.batch, n_in, n_out)
-                self.last_loss[i], G = loss_and_gradient(self.x[i], X, y, n_in, n_hidden, n_out)
+                self.last_loss[i], G, amb = loss_and_gradient(self.x[i], X, y, n_in, n_hidden, n_out, self.margin)
+                self.ambiguous[i].update(int(n) for n in amb)
                 g = G + self.wd * self.x[i]
                 self.v[i] = self.mu * self.v[i] + g
                 self.x[i] = self.x[i] - self.lr * self.v[i]
             self.step += 1
+
+    def certain_mask(self):
+        """[W][d] bool: False on the parameters (column n of W1, b1[n]) fed by a borderline relu unit
+        since the last clear_ambiguous()."""
+        n_in, n_hidden, n_out = self.shape
+        mask = np.ones((self.W, self.d), dtype=bool)
+        for i, units in enumerate(self.ambiguous):
+            for n in units:
+                mask[i, n:n_in * n_hidden:n_hidden] = False
+                mask[i, n_in * n_hidden + n] = False
+        return mask
+
+    def clear_ambiguous(self):
+        self.ambiguous = [set() for _ in range(self.W)]
 
     def average_begin(self):
         assert not self.averaging

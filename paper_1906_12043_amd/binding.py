@@ -73,6 +73,7 @@ def lib():
             "cocod_is_averaging": ([vp], i32),
             "cocod_get_plan": ([vp, P(u64), P(u32), P(u32)], i32),
             "cocod_fill_quadratic": ([vp], i32),
+            "cocod_mlp_workspace": ([vp, P(vp), P(vp), P(vp), P(vp), P(vp), P(u32)], i32),
             "cocod_step_timing": ([vp, i32], i32),
             "cocod_step_timing_read": ([vp, P(C.c_double), P(u32)], i32),
             "cocod_debug_copy": ([vp, vp, vp, u64], i32),
@@ -253,6 +254,13 @@ class Context:
         total, n = (C.c_double * 2)(), (C.c_uint32 * 2)()
         _check(lib().cocod_step_timing_read(self.handle, total, n), self.handle)
         return [(total[0], n[0]), (total[1], n[1])]
+
+    def mlp_workspace(self):
+        """Device addresses {X, H, dA, dZ, y} of the MLP work space and the row pitch of dZ."""
+        ptrs = [C.c_void_p() for _ in range(5)]
+        pitch = C.c_uint32()
+        _check(lib().cocod_mlp_workspace(self.handle, *[C.byref(q) for q in ptrs], C.byref(pitch)), self.handle)
+        return dict(zip(("X", "H", "dA", "dZ", "y"), [q.value for q in ptrs])), pitch.value
 
     def fill_quadratic(self):
         return _check(lib().cocod_fill_quadratic(self.handle), self.handle)

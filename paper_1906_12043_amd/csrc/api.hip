@@ -22,6 +22,8 @@ struct cocod_ctx {
     std::vector<Chunk> chunks;
     Chunk *d_chunks = nullptr;          // device copy of the chunk table (owned)
     float *d_weights = nullptr;         // device copy of p_i (owned), nullptr = uniform
+    float *mlp_ws = nullptr;            // MLP kind: work space (owned); mlp holds the pointers carved from it
+    cocod::MlpParams mlp{};
     hipEvent_t ev_snap = nullptr;       // compute stream reached the point where the models are stored
     hipEvent_t ev_mean = nullptr;       // mean of the stored models is complete
     hipStream_t s_compute = nullptr, s_avg = nullptr;
@@ -155,8 +157,18 @@ int validate(const cocod_config *cfg, uint64_t padded_d)
         }
         if (std::fabs(sum - 1.0) > 1e-4) return fail(nullptr, COCOD_ERR_INVALID, "weights sum to %g, not 1", sum);
     }
-    if (cfg->grad == COCOD_GRAD_MLP)
-        return fail(nullptr, COCOD_ERR_UNSUPPORTED, "the MLP gradient is not built into this library version");
+    if (cfg->grad == COCOD_GRAD_MLP) {
+        const uint64_t want = static_cast<uint64_t>(cfg->mlp_in) * cfg->mlp_hidden + cfg->mlp_hidden +
+                              static_cast<uint64_t>(cfg->mlp_hidden) * cfg->mlp_out + cfg->mlp_out;
+        if (cfg->d != want)
+            return fail(nullptr, COCOD_ERR_INVALID, "d is %llu but the MLP has %llu parameters",
+                        (unsigned long long)cfg->d, (unsigned long long)want);
+        if (cfg->n_tensors > 1) return fail(nullptr, COCOD_ERR_INVALID, "the MLP parameters are one flat tensor");
+        if (!cocod::mlp_shape_supported(cfg->mlp_in, cfg->mlp_hidden, cfg->mlp_out, cfg->mlp_batch))
+            return fail(nullptr, COCOD_ERR_UNSUPPORTED,
+                        "MLP shape: mlp_in and mlp_batch must be multiples of 128 (batch <= 1024), mlp_hidden a "
+                        "multiple of 64, 1 <= mlp_out <= 16");
+    }
     return COCOD_OK;
 }
 
@@ -165,6 +177,7 @@ void release(cocod_ctx *ctx)
     if (!ctx->dry) {
         if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
         if (ctx->d_weights) (void)hipFree(ctx->d_weights);
+        if (ctx->mlp_ws) (void)hipFree(ctx->mlp_ws);
         if (ctx->ev_snap) (void)hipEventDestroy(ctx->ev_snap);
         if (ctx->ev_mean) (void)hipEventDestroy(ctx->ev_mean);
         for (hipEvent_t e : ctx->t_start) (void)hipEventDestroy(e);
@@ -254,6 +267,20 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
             if (e == hipSuccess)
                 e = hipMemcpy(ctx->d_weights, weights.data(), weights.size() * sizeof(float), hipMemcpyHostToDevice);
         }
+        if (e == hipSuccess && cfg->grad == COCOD_GRAD_MLP) {      // one work-space block, carved below
+            const size_t wb = static_cast<size_t>(cfg->W) * cfg->mlp_batch;
+            const size_t n_x = wb * cfg->mlp_in, n_h = wb * cfg->mlp_hidden, n_z = wb * cocod::mlp_dz_pitch();
+            e = hipMalloc(reinterpret_cast<void **>(&ctx->mlp_ws), (2 * n_x + 2 * n_h + n_z + wb) * sizeof(float));
+            if (e == hipSuccess) {
+                float *at = ctx->mlp_ws;
+                ctx->mlp.X = at;  at += n_x;
+                ctx->mlp.XT = at; at += n_x;
+                ctx->mlp.H = at;  at += n_h;
+                ctx->mlp.dA = at; at += n_h;
+                ctx->mlp.dZ = at; at += n_z;
+                ctx->mlp.y = reinterpret_cast<int32_t *>(at);
+            }
+        }
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_snap, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_mean, hipEventDisableTiming);
         if (e != hipSuccess) {
@@ -295,7 +322,29 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6)
     // Keep the stored models intact: the first step of an open round reads them and
     // writes the spare buffer, which then becomes the live one.
     float *dst = ctx->store_pending ? ctx->spare : ctx->live;
-    if (!ctx->dry) {
+    if (!ctx->dry && ctx->cfg.grad == COCOD_GRAD_MLP) {
+        cocod::MlpParams p = ctx->mlp;             // work-space pointers
+        p.W = ctx->cfg.W;
+        p.n_in = ctx->cfg.mlp_in; p.n_hid = ctx->cfg.mlp_hidden; p.n_out = ctx->cfg.mlp_out; p.batch = ctx->cfg.mlp_batch;
+        p.stride = ctx->cfg.stride;
+        p.x_in = ctx->live;
+        p.x_out = dst;
+        p.v = ctx->cfg.v;
+        p.lr = ctx->cfg.lr;
+        p.momentum = ctx->cfg.momentum;
+        p.weight_decay = ctx->cfg.weight_decay;
+        p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
+        p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
+        p.step = static_cast<uint32_t>(ctx->step);
+        const bool timed = ctx->timing && ctx->t_used < ctx->t_start.size();
+        if (timed) COCOD_HIP(ctx, hipEventRecord(ctx->t_start[ctx->t_used], ctx->s_compute));
+        COCOD_HIP(ctx, cocod::launch_mlp_step(ctx->s_compute, p));
+        if (timed) {
+            COCOD_HIP(ctx, hipEventRecord(ctx->t_stop[ctx->t_used], ctx->s_compute));
+            ctx->t_kind[ctx->t_used] = 0;
+            ctx->t_used += 1;
+        }
+    } else if (!ctx->dry) {
         cocod::StepParams p{};
         p.table = ctx->d_chunks;
         p.n_chunks = static_cast<uint32_t>(ctx->chunks.size());
@@ -356,6 +405,10 @@ int cocod_local_steps_end_apply(cocod_ctx *ctx, int k)
     int rc = check_steps(ctx, k);
     if (rc != COCOD_OK) return rc;
     if (k == 0) return cocod_average_end_apply(ctx);
+    if (ctx->cfg.grad == COCOD_GRAD_MLP) {      // the MLP step has no line-6 epilogue: separate kernel
+        for (int s = 0; s < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
+        return rc == COCOD_OK ? cocod_average_end_apply(ctx) : rc;
+    }
     for (int s = 0; s + 1 < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
     if (rc != COCOD_OK) return rc;
     if (!ctx->dry) {
@@ -511,6 +564,19 @@ int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches
         launches[kind] += 1;
     }
     ctx->t_used = 0;
+    return COCOD_OK;
+}
+
+int cocod_mlp_workspace(const cocod_ctx *ctx, float **X, float **H, float **dA, float **dZ, int32_t **y, uint32_t *dz_pitch)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (ctx->cfg.grad != COCOD_GRAD_MLP) return fail(nullptr, COCOD_ERR_INVALID, "not an MLP-gradient context");
+    if (X) *X = ctx->mlp.X;
+    if (H) *H = ctx->mlp.H;
+    if (dA) *dA = ctx->mlp.dA;
+    if (dZ) *dZ = ctx->mlp.dZ;
+    if (y) *y = ctx->mlp.y;
+    if (dz_pitch) *dz_pitch = static_cast<uint32_t>(cocod::mlp_dz_pitch());
     return COCOD_OK;
 }
 

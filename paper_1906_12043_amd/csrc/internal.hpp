@@ -59,6 +59,28 @@ hipError_t launch_fill_quadratic(hipStream_t stream, const Chunk *table, uint32_
                                  uint64_t stride, uint64_t padded_d, float *h, float *c,
                                  uint32_t key0, uint32_t key1);
 
+// One local step of W perceptron workers (MLP gradient kind).
+struct MlpParams {
+    uint32_t W, n_in, n_hid, n_out, batch;
+    uint64_t stride;          // elements between workers in x_in / x_out / v
+    const float *x_in;        // flat parameters W1 | b1 | W2 | b2 per worker
+    float *x_out;             // == x_in for an in-place step
+    float *v;                 // momentum, unused when momentum == 0
+    float lr, momentum, weight_decay;
+    uint32_t key0, key1, step;
+    // work space owned by the context
+    float *X;                 // [W][batch][n_in]
+    float *XT;                // [W][n_in][batch]
+    float *H;                 // [W][batch][n_hid]  relu output
+    float *dA;                // [W][batch][n_hid]  gradient at the hidden pre-activation
+    float *dZ;                // [W][batch][mlp_dz_pitch()]  gradient at the logits
+    int32_t *y;               // [W][batch] labels
+};
+
+bool mlp_shape_supported(uint32_t n_in, uint32_t n_hid, uint32_t n_out, uint32_t batch);
+size_t mlp_dz_pitch();
+hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p);
+
 hipError_t launch_copy(hipStream_t stream, const float *src, float *dst, uint64_t n_quads);
 
 hipError_t launch_debug_normals(hipStream_t stream, uint32_t key0, uint32_t key1, uint32_t tag,

@@ -81,6 +81,33 @@ def test_minibatch_streams():
     assert not np.array_equal(X, X2) and not np.array_equal(y, y2)
 
 
+def test_borderline_relu_unit_touches_one_column_only():
+    """Taking the other relu branch at a pre-activation of ~0 changes column n of dW1 and db1[n] and
+    nothing else (H is ~0 either way); loss_and_gradient reports exactly those units."""
+    n_in, n_hidden, n_out = SHAPE
+    theta, X, y = small_problem(seed=8, batch=6)
+    W1, b1, W2, b2 = mlp.split(theta, *SHAPE)
+    b, n = 2, 5
+    A = X @ W1 + b1
+    grads = []
+    for eps in (+1e-9, -1e-9):                       # put A[b][n] just above / just below zero
+        th = theta.copy()
+        th[n_in * n_hidden + n] += -A[b, n] + eps
+        # other samples of unit n move too; keep them away from zero so only (b, n) is borderline
+        loss, g, amb = mlp.loss_and_gradient(th, X, y, *SHAPE, margin=1e-6)
+        assert list(amb) == [n]
+        grads.append(g)
+    diff = np.abs(grads[0] - grads[1])
+    touched = np.zeros(theta.size, dtype=bool)
+    touched[n:n_in * n_hidden:n_hidden] = True
+    touched[n_in * n_hidden + n] = True
+    assert diff[touched].max() > 1e-4 and diff[~touched].max() < 1e-9
+    o = make(2)
+    o.ambiguous[1].add(3)
+    mask = o.certain_mask()
+    assert mask[0].all() and (~mask[1]).sum() == 16 + 1 and not mask[1, 3] and not mask[1, 16 * 8 + 3]
+
+
 def make(W, shape=(16, 8, 4), batch=8, **kw):
     theta0 = synth_inputs.mlp_he_init(1, *shape)
     hyper = dict(lr=0.05, momentum=0.9, weight_decay=1e-3, seed=9)
