@@ -270,11 +270,10 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         if (e == hipSuccess && cfg->grad == COCOD_GRAD_MLP) {      // one work-space block, carved below
             const size_t wb = static_cast<size_t>(cfg->W) * cfg->mlp_batch;
             const size_t n_x = wb * cfg->mlp_in, n_h = wb * cfg->mlp_hidden, n_z = wb * cocod::mlp_dz_pitch();
-            e = hipMalloc(reinterpret_cast<void **>(&ctx->mlp_ws), (2 * n_x + 2 * n_h + n_z + wb) * sizeof(float));
+            e = hipMalloc(reinterpret_cast<void **>(&ctx->mlp_ws), (n_x + 2 * n_h + n_z + wb) * sizeof(float));
             if (e == hipSuccess) {
                 float *at = ctx->mlp_ws;
                 ctx->mlp.X = at;  at += n_x;
-                ctx->mlp.XT = at; at += n_x;
                 ctx->mlp.H = at;  at += n_h;
                 ctx->mlp.dA = at; at += n_h;
                 ctx->mlp.dZ = at; at += n_z;

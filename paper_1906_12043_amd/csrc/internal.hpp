@@ -70,7 +70,6 @@ struct MlpParams {
     uint32_t key0, key1, step;
     // work space owned by the context
     float *X;                 // [W][batch][n_in]
-    float *XT;                // [W][n_in][batch]
     float *H;                 // [W][batch][n_hid]  relu output
     float *dA;                // [W][batch][n_hid]  gradient at the hidden pre-activation
     float *dZ;                // [W][batch][mlp_dz_pitch()]  gradient at the logits

@@ -3,7 +3,7 @@
 // on a fresh seeded mini-batch per (worker, step); all W workers advance in the same launches.
 //
 // One local step = six launches on the compute stream:
-//   gen_batch      X, X^T, labels from the counter-based generator              (vector ALU)
+//   gen_batch      X and labels from the counter-based generator                 (vector ALU)
 //   gemm<FWD>      H = relu(X W1 + b1)                         [B x in] x [in x hid]   fp32 MFMA
 //   head_logits    Z = H W2 + b2, softmax, dZ = (P - onehot)/B  (one wave per sample, wave reductions)
 //   head_backprop  dA = (dZ W2^T) * [H > 0]
@@ -13,12 +13,18 @@
 // The two big contractions (98 % of the flops) run on the matrix cores; the output layer has
 // 10 columns and stays on the vector units.
 //
-// GEMM kernel: 128 x 64 output tile per 256-thread block, K in slices of 16 staged through LDS with
-// register prefetch (double buffered); each of the 4 waves owns 32 rows x 64 columns = two
-// 32x32x2 fp32 MFMA accumulators.  Both GEMMs read A with K contiguous and B with N contiguous
-// (that is why the generator also writes X^T), so one kernel serves both with two epilogues.
+// GEMM kernel: 64 x 128 output tile per 512-thread block (8 waves, one 32x32 accumulator each; 64 x 64
+// with 4 waves when the hidden width is not a multiple of 128).  K goes through LDS in slices
+// of 32 with register prefetch and two buffers (one barrier per slice); a wave reads all fragments
+// of a slice before it starts the slice's chain of 16 MFMAs.  The forward product reads
+// its A operand K-contiguous; the backward product needs X^T and gets it by staging X through LDS
+// transposed, so no transposed copy of the mini-batch is ever written.  After the K loop the
+// accumulators pass through LDS once more so that the epilogue touches memory in 16-byte pieces
+// along rows (256 contiguous bytes per row per wave) instead of 4-byte pieces along columns.
 #include "internal.hpp"
 #include "philox.hpp"
+
+#include <type_traits>
 
 namespace cocod {
 namespace {
@@ -26,7 +32,9 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128, kBN = 64, kBK = 16, kGemmThreads = 256;
+constexpr int kBK = 32;               // K slice staged through LDS
+constexpr int kAPitch = kBK + 1;      // odd pitch: conflict-free fragment reads
+constexpr int kShapeM = 128, kShapeN = 64;   // shape contract: n_in, batch multiples of 128; n_hid of 64
 constexpr int kMaxOut = 16;
 
 struct Offsets { uint64_t W1, b1, W2, b2; };
@@ -54,7 +62,7 @@ __device__ __forceinline__ void sgd_update(const MlpParams &p, uint64_t at, floa
 }
 
 // ---- mini-batch ---------------------------------------------------------------------------------
-// X[b][f] = normal(stream X, worker, step, flat index b*n_in + f); also stored transposed.
+// X[b][f] = normal(stream X, worker, step, flat index b*n_in + f);
 // y[b] = (word * n_out) >> 32 from stream Y at index b.
 __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
 {
@@ -63,13 +71,8 @@ __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
     const uint64_t q = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (q < n_quads) {
         const Normals4 z = box_muller_fast(philox4x32_10(static_cast<uint32_t>(q), p.step, worker, kTagMlpX, p.key0, p.key1));
-        const uint64_t flat = q * 4;
-        const uint32_t b = static_cast<uint32_t>(flat / p.n_in), f = static_cast<uint32_t>(flat % p.n_in);
         float *X = p.X + static_cast<uint64_t>(worker) * p.batch * p.n_in;
-        float *XT = p.XT + static_cast<uint64_t>(worker) * p.batch * p.n_in;
-        *reinterpret_cast<f4 *>(X + flat) = f4{z.z[0], z.z[1], z.z[2], z.z[3]};
-        #pragma unroll
-        for (int i = 0; i < 4; ++i) XT[static_cast<uint64_t>(f + i) * p.batch + b] = z.z[i];
+        *reinterpret_cast<f4 *>(X + q * 4) = f4{z.z[0], z.z[1], z.z[2], z.z[3]};
     }
     if (blockIdx.x == 0 && threadIdx.x < p.batch / 4) {
         const Words4 r = philox4x32_10(threadIdx.x, p.step, worker, kTagMlpY, p.key0, p.key1);
@@ -83,87 +86,177 @@ __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
 // ---- the two big contractions ---------------------------------------------------------------------
 enum { kFwd = 0, kBwd = 1 };
 
-template <int EPI>
-__global__ __launch_bounds__(kGemmThreads) void mlp_gemm_kernel(const MlpParams p)
+// NWM x NWN waves per block, one 32x32 accumulator per wave: block tile (32 NWM) x (32 NWN).
+template <int EPI, int NWM, int NWN>
+__global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParams p)
 {
-    __shared__ float As[2][kBM][kBK + 1];      // [m][k], odd row pitch: conflict-free fragment reads
-    __shared__ __attribute__((aligned(16))) float Bs[2][kBK][kBN + 4];      // [k][n], rows stay 16-byte aligned
+    constexpr int BM = 32 * NWM, BN = 32 * NWN, THREADS = 64 * NWM * NWN;
+    constexpr int BPITCH = BN + 4, CPITCH = BN + 4;            // rows stay 16-byte aligned
+    constexpr int STAGE = 2 * BM * kAPitch + 2 * kBK * BPITCH, TILE = BM * CPITCH;
+    __shared__ __attribute__((aligned(16))) float smem[STAGE > TILE ? STAGE : TILE];
+    float (*As)[BM][kAPitch] = reinterpret_cast<float (*)[BM][kAPitch]>(smem);                    // [buf][m][k]
+    float (*Bs)[kBK][BPITCH] = reinterpret_cast<float (*)[kBK][BPITCH]>(smem + 2 * BM * kAPitch);  // [buf][k][n]
+    float (*Ct)[CPITCH] = reinterpret_cast<float (*)[CPITCH]>(smem);                               // epilogue tile
 
     const uint32_t worker = blockIdx.z;
-    const uint32_t m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
+    const uint32_t m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const Offsets o = offsets_of(p);
-    const float *A, *B;
-    uint32_t lda, K;
-    const uint32_t ldb = p.n_hid;
-    if (EPI == kFwd) {          // X [batch][n_in] times W1 [n_in][n_hid]
-        A = p.X + static_cast<uint64_t>(worker) * p.batch * p.n_in;
-        B = p.x_in + static_cast<uint64_t>(worker) * p.stride + o.W1;
-        lda = p.n_in; K = p.n_in;
-    } else {                    // X^T [n_in][batch] times dA [batch][n_hid]
-        A = p.XT + static_cast<uint64_t>(worker) * p.batch * p.n_in;
-        B = p.dA + static_cast<uint64_t>(worker) * p.batch * p.n_hid;
-        lda = p.batch; K = p.batch;
-    }
-
     const uint32_t t = threadIdx.x;
-    // global -> register staging: A tile 128 x 16 = 512 quads (2 per thread), B tile 16 x 64 = 256 quads
-    const uint32_t a_m = t / 4, a_k = (t % 4) * 4;
-    const uint32_t b_k = t / 16, b_n = (t % 16) * 4;
-    const float *a_src0 = A + static_cast<uint64_t>(m0 + a_m) * lda + a_k;
-    const float *a_src1 = A + static_cast<uint64_t>(m0 + a_m + 64) * lda + a_k;
-    const float *b_src = B + static_cast<uint64_t>(b_k) * ldb + n0 + b_n;
+    const uint32_t ldb = p.n_hid;
+    const float *Xw = p.X + static_cast<uint64_t>(worker) * p.batch * p.n_in;
 
-    f4 ra0 = *reinterpret_cast<const f4 *>(a_src0);
-    f4 ra1 = *reinterpret_cast<const f4 *>(a_src1);
-    f4 rb = *reinterpret_cast<const f4 *>(b_src);
-
-    const uint32_t wave = t / 64, lane = t % 64;
-    const uint32_t frag_m = wave * 32 + lane % 32, frag_k = lane / 32, frag_n = lane % 32;
-    f16v acc0 = {0}, acc1 = {0};
-
-    const uint32_t n_slices = K / kBK;
-    for (uint32_t s = 0; s < n_slices; ++s) {
-        const uint32_t cur = s & 1;
-        #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            As[cur][a_m][a_k + i] = ra0[i];
-            As[cur][a_m + 64][a_k + i] = ra1[i];
-        }
-        *reinterpret_cast<f4 *>(&Bs[cur][b_k][b_n]) = rb;
-        __syncthreads();        // slice s visible; everyone is done reading buffer cur from slice s-2
-        if (s + 1 < n_slices) { // prefetch the next slice while this one is multiplied
-            ra0 = *reinterpret_cast<const f4 *>(a_src0 + static_cast<uint64_t>(s + 1) * kBK);
-            ra1 = *reinterpret_cast<const f4 *>(a_src1 + static_cast<uint64_t>(s + 1) * kBK);
-            rb = *reinterpret_cast<const f4 *>(b_src + static_cast<uint64_t>(s + 1) * kBK * ldb);
-        }
-        #pragma unroll
-        for (int kk = 0; kk < kBK; kk += 2) {
-            const float a = As[cur][frag_m][kk + frag_k];
-            const float b0 = Bs[cur][kk + frag_k][frag_n];
-            const float b1 = Bs[cur][kk + frag_k][frag_n + 32];
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
-        }
-        // no second barrier: the next iteration writes the OTHER buffer, and the barrier inside it
-        // orders those writes against the reads of the iteration after
+    // Global -> register staging of one K slice, in 16-byte quads.
+    //   forward : A = X [batch][n_in], K-contiguous: a quad is 4 consecutive k of one row m
+    //   backward: A = X^T, read from X M-contiguous: a quad is 4 consecutive rows m of one sample k
+    //   B tile  : kBK x BN, N-contiguous (W1 rows, or dA rows)
+    constexpr int A_QUADS = BM * kBK / 4, PA = A_QUADS / THREADS;
+    constexpr int B_QUADS = kBK * BN / 4, PB = B_QUADS / THREADS;
+    static_assert(PA * THREADS == A_QUADS && PB * THREADS == B_QUADS, "tile must split evenly over the block");
+    constexpr int A_MINOR = (EPI == kFwd) ? kBK / 4 : BM / 4;   // quads along the contiguous direction
+    constexpr int A_MAJOR_PER_PASS = THREADS / A_MINOR;
+    constexpr int B_K_PER_PASS = THREADS / (BN / 4);
+    const uint32_t a_minor = (t % A_MINOR) * 4, a_major = t / A_MINOR;
+    const uint32_t b_n = (t % (BN / 4)) * 4, b_k = t / (BN / 4);
+    const float *a_src, *b_src;
+    uint64_t a_slice, a_pass;    // element strides of A per K slice and per staging pass
+    uint32_t K;
+    if (EPI == kFwd) {
+        a_src = Xw + static_cast<uint64_t>(m0 + a_major) * p.n_in + a_minor;
+        a_slice = kBK; a_pass = static_cast<uint64_t>(A_MAJOR_PER_PASS) * p.n_in;
+        K = p.n_in;
+        b_src = p.x_in + static_cast<uint64_t>(worker) * p.stride + o.W1;                 // W1 [n_in][n_hid]
+    } else {
+        a_src = Xw + static_cast<uint64_t>(a_major) * p.n_in + m0 + a_minor;
+        a_slice = static_cast<uint64_t>(kBK) * p.n_in; a_pass = static_cast<uint64_t>(A_MAJOR_PER_PASS) * p.n_in;
+        K = p.batch;
+        b_src = p.dA + static_cast<uint64_t>(worker) * p.batch * p.n_hid;                 // dA [batch][n_hid]
     }
+    b_src += static_cast<uint64_t>(b_k) * ldb + n0 + b_n;
 
-    // accumulator layout of the 32x32 tile: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const uint32_t row = m0 + wave * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+    // Forward product: two sets of staging registers, so global loads run two K slices ahead of their
+    // use; that covers the HBM latency of the weight stream (one slice of MFMAs is shorter than it).
+    // Backward product: K is only the batch (4 slices); one set keeps the registers, and with them
+    // the number of resident blocks, where the memory-bound epilogue wants them.
+    constexpr int NSETS = (EPI == kFwd) ? 2 : 1;
+    f4 ra[NSETS][PA], rb[NSETS][PB];
+    auto load_slice = [&](auto set, uint32_t slice) {
+        constexpr int S = decltype(set)::value;
         #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const uint32_t col = n0 + 32 * half + lane % 32;
-            const float val = half ? acc1[r] : acc0[r];
-            if (EPI == kFwd) {
-                const float bias = p.x_in[static_cast<uint64_t>(worker) * p.stride + o.b1 + col];
-                p.H[(static_cast<uint64_t>(worker) * p.batch + row) * p.n_hid + col] = fmaxf(val + bias, 0.0f);
-            } else {
-                sgd_update(p, static_cast<uint64_t>(worker) * p.stride + o.W1 + static_cast<uint64_t>(row) * p.n_hid + col, val);
+        for (int i = 0; i < PA; ++i) ra[S][i] = *reinterpret_cast<const f4 *>(a_src + slice * a_slice + i * a_pass);
+        #pragma unroll
+        for (int i = 0; i < PB; ++i)
+            rb[S][i] = *reinterpret_cast<const f4 *>(b_src + (static_cast<uint64_t>(slice) * kBK + static_cast<uint64_t>(i) * B_K_PER_PASS) * ldb);
+    };
+    auto stage_to_lds = [&](auto set, uint32_t buf) {
+        constexpr int S = decltype(set)::value;
+        #pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const uint32_t major = a_major + i * A_MAJOR_PER_PASS;
+            #pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (EPI == kFwd) As[buf][major][a_minor + j] = ra[S][i][j];      // (row, k)
+                else             As[buf][a_minor + j][major] = ra[S][i][j];      // transposed on the way in
             }
         }
+        #pragma unroll
+        for (int i = 0; i < PB; ++i) *reinterpret_cast<f4 *>(&Bs[buf][b_k + i * B_K_PER_PASS][b_n]) = rb[S][i];
+    };
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, 1>;
+
+    const uint32_t wave = t / 64, lane = t % 64;
+    const uint32_t wm = wave % NWM, wn = wave / NWM;             // wave owns rows 32 wm .., columns 32 wn ..
+    const uint32_t frag_m = wm * 32 + lane % 32, frag_k = lane / 32, frag_n = wn * 32 + lane % 32;
+    f16v acc = {0};
+
+    // Backward product: the epilogue updates this block's tile of W1 and its momentum.
+    // Their loads are issued now, so the memory latency hides behind the whole K loop.
+    constexpr int EPI_ITERS = (BM * BN / 4) / THREADS;
+    f4 x_old[EPI_ITERS], v_old[EPI_ITERS];
+    if (EPI == kBwd) {
+        #pragma unroll
+        for (int it = 0; it < EPI_ITERS; ++it) {
+            const uint32_t idx = it * THREADS + t;
+            const uint64_t at = static_cast<uint64_t>(worker) * p.stride + o.W1 +
+                                static_cast<uint64_t>(m0 + idx / (BN / 4)) * p.n_hid + n0 + (idx % (BN / 4)) * 4;
+            x_old[it] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.x_in + at));
+            v_old[it] = p.momentum != 0.0f ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.v + at)) : f4{0.f, 0.f, 0.f, 0.f};
+        }
     }
+
+    // Software pipeline over the K slices (their number is a multiple of 4 by the shape contract).
+    // At the top of iteration s: slice s sits in LDS buffer s&1, visible to all waves; slice s+1
+    // sits in a register set; with two sets the loads of slice s+2 into the other set are in flight.
+    // The iteration reads its fragments, pushes slice s+1 into the other LDS buffer and starts the
+    // loads of the next slice to fetch BEFORE the chain of 16 MFMAs, so all of that runs under the
+    // multiplies; one barrier per slice.
+    const uint32_t n_slices = K / kBK;
+    auto iteration = [&](auto next_set, uint32_t s) {
+        const uint32_t cur = s & 1;
+        float af[kBK / 2], bf[kBK / 2];
+        #pragma unroll
+        for (int i = 0; i < kBK / 2; ++i) {
+            af[i] = As[cur][frag_m][2 * i + frag_k];
+            bf[i] = Bs[cur][2 * i + frag_k][frag_n];
+        }
+        if (s + 1 < n_slices) stage_to_lds(next_set, cur ^ 1);   // buffer last read in iteration s-1, before its barrier
+        if (s + 1 + NSETS < n_slices) load_slice(next_set, s + 1 + NSETS);
+        #pragma unroll
+        for (int i = 0; i < kBK / 2; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[i], acc, 0, 0, 0);
+        __syncthreads();        // slice s+1 visible; everyone is done reading buffer cur
+    };
+    load_slice(Set0{}, 0);
+    if constexpr (NSETS == 2) {
+        load_slice(Set1{}, 1);
+        stage_to_lds(Set0{}, 0);
+        load_slice(Set0{}, 2);
+        __syncthreads();
+        for (uint32_t s = 0; s < n_slices; s += 2) {
+            iteration(Set1{}, s);
+            iteration(Set0{}, s + 1);
+        }
+    } else {
+        stage_to_lds(Set0{}, 0);
+        load_slice(Set0{}, 1);
+        __syncthreads();
+        for (uint32_t s = 0; s < n_slices; ++s) iteration(Set0{}, s);
+    }
+
+    // accumulators -> LDS tile.  Register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of the 32x32 block.
+    // (the loop's last barrier already guarantees that the staging buffers are dead)
+    #pragma unroll
+    for (int r = 0; r < 16; ++r)
+        Ct[wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4)][wn * 32 + lane % 32] = acc[r];
+    __syncthreads();
+
+    // epilogue over the tile in row-major quads: BN/4 lanes cover one row
+    #pragma unroll
+    for (int it = 0; it < EPI_ITERS; ++it) {
+        const uint32_t idx = it * THREADS + t;
+        const uint32_t row = idx / (BN / 4), col = (idx % (BN / 4)) * 4;
+        const f4 val = *reinterpret_cast<const f4 *>(&Ct[row][col]);
+        if (EPI == kFwd) {
+            const f4 bias = *reinterpret_cast<const f4 *>(p.x_in + static_cast<uint64_t>(worker) * p.stride + o.b1 + n0 + col);
+            f4 h = val + bias;
+            h.x = fmaxf(h.x, 0.f); h.y = fmaxf(h.y, 0.f); h.z = fmaxf(h.z, 0.f); h.w = fmaxf(h.w, 0.f);
+            *reinterpret_cast<f4 *>(p.H + (static_cast<uint64_t>(worker) * p.batch + m0 + row) * p.n_hid + n0 + col) = h;
+        } else {
+            const uint64_t at = static_cast<uint64_t>(worker) * p.stride + o.W1 + static_cast<uint64_t>(m0 + row) * p.n_hid + n0 + col;
+            f4 g = val + p.weight_decay * x_old[it];
+            if (p.momentum != 0.0f) {
+                g = p.momentum * v_old[it] + g;
+                __builtin_nontemporal_store(g, reinterpret_cast<f4 *>(p.v + at));
+            }
+            __builtin_nontemporal_store(x_old[it] - p.lr * g, reinterpret_cast<f4 *>(p.x_out + at));
+        }
+    }
+}
+
+template <int EPI, int NWM, int NWN>
+void launch_gemm(hipStream_t stream, const MlpParams &p)
+{
+    const uint32_t M = (EPI == kFwd) ? p.batch : p.n_in;
+    hipLaunchKernelGGL((mlp_gemm_kernel<EPI, NWM, NWN>), dim3(p.n_hid / (32 * NWN), M / (32 * NWM), p.W), dim3(64 * NWM * NWN), 0, stream, p);
 }
 
 // ---- output layer -----------------------------------------------------------------------------------
@@ -236,20 +329,24 @@ __global__ __launch_bounds__(256) void head_backprop_kernel(const MlpParams p)
     }
 }
 
-// Gradients of the small parameters and their update: a thread owns hidden unit n
-// (row n of W2 and b1[n]); block 0 of a worker also owns b2 and the alignment pads.
-__global__ __launch_bounds__(64) void head_update_kernel(const MlpParams p)
+// Gradients of the small parameters and their update.  A block owns 64 hidden units (row n of W2 and
+// b1[n]); its four waves each sum a quarter of the batch and the partial sums meet in LDS in a fixed
+// order.  Block 0 of a worker also owns b2 and the alignment pads.
+__global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
 {
+    __shared__ float part[4][64][kMaxOut + 1];
     const uint32_t worker = blockIdx.y;
-    const uint32_t n = blockIdx.x * 64 + threadIdx.x;
+    const uint32_t u = threadIdx.x % 64, slice = threadIdx.x / 64;
+    const uint32_t n = blockIdx.x * 64 + u;
     const Offsets o = offsets_of(p);
     const uint64_t base = static_cast<uint64_t>(worker) * p.stride;
+    float gw[kMaxOut];
+    #pragma unroll
+    for (int c = 0; c < kMaxOut; ++c) gw[c] = 0.0f;
+    float gb = 0.0f;
     if (n < p.n_hid) {
-        float gw[kMaxOut];
-        #pragma unroll
-        for (int c = 0; c < kMaxOut; ++c) gw[c] = 0.0f;
-        float gb = 0.0f;
-        for (uint32_t b = 0; b < p.batch; ++b) {
+        const uint32_t per = p.batch / 4;
+        for (uint32_t b = slice * per; b < (slice + 1) * per; ++b) {
             const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b;
             const float hv = p.H[sample * p.n_hid + n];
             gb += p.dA[sample * p.n_hid + n];
@@ -258,20 +355,28 @@ __global__ __launch_bounds__(64) void head_update_kernel(const MlpParams p)
             for (int c = 0; c < kMaxOut; ++c)
                 if (c < static_cast<int>(p.n_out)) gw[c] += hv * dz[c];
         }
+    }
+    #pragma unroll
+    for (int c = 0; c < kMaxOut; ++c) part[slice][u][c] = gw[c];
+    part[slice][u][kMaxOut] = gb;
+    __syncthreads();
+    if (slice == 0 && n < p.n_hid) {
         #pragma unroll
         for (int c = 0; c < kMaxOut; ++c)
-            if (c < static_cast<int>(p.n_out)) sgd_update(p, base + o.W2 + static_cast<uint64_t>(n) * p.n_out + c, gw[c]);
-        sgd_update(p, base + o.b1 + n, gb);
+            if (c < static_cast<int>(p.n_out))
+                sgd_update(p, base + o.W2 + static_cast<uint64_t>(n) * p.n_out + c,
+                           ((part[0][u][c] + part[1][u][c]) + part[2][u][c]) + part[3][u][c]);
+        sgd_update(p, base + o.b1 + n, ((part[0][u][kMaxOut] + part[1][u][kMaxOut]) + part[2][u][kMaxOut]) + part[3][u][kMaxOut]);
     }
-    if (blockIdx.x == 0) {
-        if (threadIdx.x < p.n_out) {
+    if (blockIdx.x == 0 && slice == 1) {
+        if (u < p.n_out) {
             float g = 0.0f;
             for (uint32_t b = 0; b < p.batch; ++b)
-                g += p.dZ[(static_cast<uint64_t>(worker) * p.batch + b) * kMaxOut + threadIdx.x];
-            sgd_update(p, base + o.b2 + threadIdx.x, g);
+                g += p.dZ[(static_cast<uint64_t>(worker) * p.batch + b) * kMaxOut + u];
+            sgd_update(p, base + o.b2 + u, g);
         }
         const uint64_t d = o.b2 + p.n_out;                       // pads after the last parameter travel along
-        if (p.x_out != p.x_in && threadIdx.x < ((d + 3) & ~3ull) - d) p.x_out[base + d + threadIdx.x] = p.x_in[base + d + threadIdx.x];
+        if (p.x_out != p.x_in && u < ((d + 3) & ~3ull) - d) p.x_out[base + d + u] = p.x_in[base + d + u];
     }
 }
 
@@ -279,9 +384,9 @@ __global__ __launch_bounds__(64) void head_update_kernel(const MlpParams p)
 
 bool mlp_shape_supported(uint32_t n_in, uint32_t n_hid, uint32_t n_out, uint32_t batch)
 {
-    return n_in >= static_cast<uint32_t>(kBM) && n_in % kBM == 0 && n_hid >= static_cast<uint32_t>(kBN) && n_hid % kBN == 0 &&
-           n_out >= 1 && n_out <= static_cast<uint32_t>(kMaxOut) && batch >= static_cast<uint32_t>(kBM) && batch % kBM == 0 &&
-           batch <= 1024;
+    return n_in >= static_cast<uint32_t>(kShapeM) && n_in % kShapeM == 0 && n_hid >= static_cast<uint32_t>(kShapeN) &&
+           n_hid % kShapeN == 0 && n_out >= 1 && n_out <= static_cast<uint32_t>(kMaxOut) &&
+           batch >= static_cast<uint32_t>(kShapeM) && batch % kShapeM == 0 && batch <= 1024;
 }
 
 size_t mlp_dz_pitch() { return kMaxOut; }
@@ -289,12 +394,13 @@ size_t mlp_dz_pitch() { return kMaxOut; }
 hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
 {
     const uint64_t n_quads = static_cast<uint64_t>(p.batch) * p.n_in / 4;
+    const bool wide = p.n_hid % 128 == 0;      // 64 x 128 block tiles (fastest measured), else 64 x 64
     hipLaunchKernelGGL(gen_batch_kernel, dim3(static_cast<uint32_t>((n_quads + 255) / 256), p.W), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL((mlp_gemm_kernel<kFwd>), dim3(p.n_hid / kBN, p.batch / kBM, p.W), dim3(kGemmThreads), 0, stream, p);
+    if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
     hipLaunchKernelGGL(head_logits_kernel, dim3((p.batch + 3) / 4, p.W), dim3(256), 0, stream, p);
     hipLaunchKernelGGL(head_backprop_kernel, dim3((p.n_hid + 255) / 256, (p.batch + 7) / 8, p.W), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(head_update_kernel, dim3((p.n_hid + 63) / 64, p.W), dim3(64), 0, stream, p);
-    hipLaunchKernelGGL((mlp_gemm_kernel<kBwd>), dim3(p.n_hid / kBN, p.n_in / kBM, p.W), dim3(kGemmThreads), 0, stream, p);
+    hipLaunchKernelGGL(head_update_kernel, dim3((p.n_hid + 63) / 64, p.W), dim3(256), 0, stream, p);
+    if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p);
     return hipGetLastError();
 }
 
