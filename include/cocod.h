@@ -53,7 +53,10 @@ typedef enum cocod_grad_kind {
     COCOD_GRAD_QUADRATIC = 0,
     /* G = gradient of the mean softmax cross-entropy of a two-layer ReLU perceptron on a fresh
        seeded mini-batch per (worker, step): a real mini-batch gradient, dense contractions. */
-    COCOD_GRAD_MLP = 1
+    COCOD_GRAD_MLP = 1,
+    /* G is computed by the caller (a real model's backward pass) and handed to cocod_external_step;
+       h, c and the MLP fields are unused. */
+    COCOD_GRAD_EXTERNAL = 2
 } cocod_grad_kind;
 
 /* How Step I is scheduled relative to Step II (the arithmetic is the same in all three). */
@@ -169,6 +172,17 @@ int cocod_average_end_apply(cocod_ctx *ctx);
  */
 int cocod_local_steps_end_apply(cocod_ctx *ctx, int k);
 
+/*
+ * Step II with the caller's stochastic gradient: one local step x = x - gamma v,
+ * v = mu v + (g + lambda x), with g [W][stride] in device memory in the same packed layout as the
+ * models (pads ignored), ordered after the work already on compute_stream; the caller makes sure g
+ * is complete on that stream and stays untouched until the step has run.  Advances t by one.  Legal
+ * for every gradient kind.  close_round != 0 also applies line 6 inside this step and closes the
+ * open round (as cocod_local_steps_end_apply does); COCOD_ERR_STATE if no round is open then.
+ * Reads x, v, g and writes x, v: 20 bytes per parameter.
+ */
+int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round);
+
 /* Choose how Step I is scheduled; only legal while IDLE.  Default COCOD_SCHED_OVERLAP. */
 int cocod_set_schedule(cocod_ctx *ctx, int schedule);
 
@@ -199,6 +213,15 @@ int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks,
  */
 int cocod_step_timing(cocod_ctx *ctx, int max_launches);
 int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches[2]);
+
+/*
+ * Diagnostic: the weighted consensus distance sum_i p_i || x^ - x^i ||^2 of the live models, with
+ * x^ = sum_i p_i x^i (the quantity that Lemma 2 of the paper bounds), over the real parameters
+ * (alignment pads excluded).  Runs a reduction on compute_stream after the work already queued
+ * there, WAITS for it and writes the scalar to *result (host).  The first call allocates a small
+ * scratch buffer owned by the context.
+ */
+int cocod_consensus_distance(cocod_ctx *ctx, double *result);
 
 /* Block the host until both streams have drained. */
 int cocod_sync(cocod_ctx *ctx);

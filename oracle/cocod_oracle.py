@@ -153,6 +153,13 @@ class QuadraticOracle:
         self.lib.oracle_correct(self.W, self.n, _p(self.x), _p(self.snap), _p(self.mean))
         self.averaging = False
 
+    def consensus_distance(self):
+        """sum_i p_i ||xbar - x_i||^2 with xbar = sum_i p_i x_i: the quantity bounded by Lemma 2."""
+        p = np.full(self.W, 1.0 / self.W) if self.p is None else self.p
+        x = self.x.astype(np.float64)
+        xbar = p @ x
+        return float(np.sum(p[:, None] * (x - xbar[None, :]) ** 2))
+
     def round(self, k):
         """One pass of the while-loop body through the single C routine."""
         self.lib.oracle_round(self.W, self.n, _p(self.idx), _p(self.x), _p(self.v), _p(self.snap),

@@ -10,7 +10,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 OK, ERR_INVALID, ERR_STATE, ERR_HIP, ERR_NOMEM, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
-GRAD_QUADRATIC, GRAD_MLP = 0, 1
+GRAD_QUADRATIC, GRAD_MLP, GRAD_EXTERNAL = 0, 1, 2
 SCHED_OVERLAP, SCHED_SERIAL, SCHED_FUSED = 0, 1, 2
 FLAG_DRY_RUN = 1
 
@@ -63,6 +63,7 @@ def lib():
             "cocod_sync": ([vp], i32),
             "cocod_local_steps": ([vp, i32], i32),
             "cocod_local_steps_end_apply": ([vp, i32], i32),
+            "cocod_external_step": ([vp, vp, i32], i32),
             "cocod_average_begin": ([vp], i32),
             "cocod_average_end_apply": ([vp], i32),
             "cocod_set_schedule": ([vp, i32], i32),
@@ -72,6 +73,7 @@ def lib():
             "cocod_live_model": ([vp, P(vp)], i32),
             "cocod_is_averaging": ([vp], i32),
             "cocod_get_plan": ([vp, P(u64), P(u32), P(u32)], i32),
+            "cocod_consensus_distance": ([vp, P(C.c_double)], i32),
             "cocod_fill_quadratic": ([vp], i32),
             "cocod_mlp_workspace": ([vp, P(vp), P(vp), P(vp), P(vp), P(vp), P(u32)], i32),
             "cocod_step_timing": ([vp, i32], i32),
@@ -205,6 +207,9 @@ class Context:
     def local_steps_end_apply(self, k):
         return _check(lib().cocod_local_steps_end_apply(self.handle, k), self.handle)
 
+    def external_step(self, g, close_round=False):
+        return _check(lib().cocod_external_step(self.handle, _addr(g), int(close_round)), self.handle)
+
     def round_fused_tail(self, k):
         """One round with line 6 applied inside the last local step."""
         self.average_begin()
@@ -254,6 +259,11 @@ class Context:
         total, n = (C.c_double * 2)(), (C.c_uint32 * 2)()
         _check(lib().cocod_step_timing_read(self.handle, total, n), self.handle)
         return [(total[0], n[0]), (total[1], n[1])]
+
+    def consensus_distance(self):
+        out = C.c_double()
+        _check(lib().cocod_consensus_distance(self.handle, C.byref(out)), self.handle)
+        return out.value
 
     def mlp_workspace(self):
         """Device addresses {X, H, dA, dZ, y} of the MLP work space and the row pitch of dZ."""

@@ -22,6 +22,7 @@ struct cocod_ctx {
     std::vector<Chunk> chunks;
     Chunk *d_chunks = nullptr;          // device copy of the chunk table (owned)
     float *d_weights = nullptr;         // device copy of p_i (owned), nullptr = uniform
+    double *d_reduce = nullptr;         // scratch of the consensus-distance reduction (owned, allocated on first use)
     float *mlp_ws = nullptr;            // MLP kind: work space (owned); mlp holds the pointers carved from it
     cocod::MlpParams mlp{};
     hipEvent_t ev_snap = nullptr;       // compute stream reached the point where the models are stored
@@ -125,7 +126,7 @@ int validate(const cocod_config *cfg, uint64_t padded_d)
     const unsigned known_flags = COCOD_FLAG_DRY_RUN;
     if (cfg->flags & ~known_flags) return fail(nullptr, COCOD_ERR_INVALID, "unknown flag bits 0x%x", cfg->flags & ~known_flags);
     if (cfg->W == 0 || cfg->W > 65535u) return fail(nullptr, COCOD_ERR_INVALID, "W must be in 1..65535");
-    if (cfg->grad != COCOD_GRAD_QUADRATIC && cfg->grad != COCOD_GRAD_MLP)
+    if (cfg->grad != COCOD_GRAD_QUADRATIC && cfg->grad != COCOD_GRAD_MLP && cfg->grad != COCOD_GRAD_EXTERNAL)
         return fail(nullptr, COCOD_ERR_INVALID, "unknown gradient kind %u", cfg->grad);
     if (cfg->stride < padded_d || (cfg->stride & 3u))
         return fail(nullptr, COCOD_ERR_INVALID, "stride %llu must be a multiple of 4 and >= padded size %llu",
@@ -178,6 +179,7 @@ void release(cocod_ctx *ctx)
         if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
         if (ctx->d_weights) (void)hipFree(ctx->d_weights);
         if (ctx->mlp_ws) (void)hipFree(ctx->mlp_ws);
+        if (ctx->d_reduce) (void)hipFree(ctx->d_reduce);
         if (ctx->ev_snap) (void)hipEventDestroy(ctx->ev_snap);
         if (ctx->ev_mean) (void)hipEventDestroy(ctx->ev_mean);
         for (hipEvent_t e : ctx->t_start) (void)hipEventDestroy(e);
@@ -316,12 +318,12 @@ int cocod_sync(cocod_ctx *ctx)
 }
 
 // One local step on the compute stream; with_line6 fuses line 6 into it (last step of a round).
-static int enqueue_step(cocod_ctx *ctx, bool with_line6)
+static int enqueue_step(cocod_ctx *ctx, bool with_line6, const float *g_ext = nullptr)
 {
     // Keep the stored models intact: the first step of an open round reads them and
     // writes the spare buffer, which then becomes the live one.
     float *dst = ctx->store_pending ? ctx->spare : ctx->live;
-    if (!ctx->dry && ctx->cfg.grad == COCOD_GRAD_MLP) {
+    if (!ctx->dry && ctx->cfg.grad == COCOD_GRAD_MLP && !g_ext) {
         cocod::MlpParams p = ctx->mlp;             // work-space pointers
         p.W = ctx->cfg.W;
         p.n_in = ctx->cfg.mlp_in; p.n_hid = ctx->cfg.mlp_hidden; p.n_out = ctx->cfg.mlp_out; p.batch = ctx->cfg.mlp_batch;
@@ -354,6 +356,7 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6)
         p.v = ctx->cfg.v;
         p.h = ctx->cfg.h;
         p.c = ctx->cfg.c;
+        p.g = g_ext;
         p.snap = with_line6 ? ctx->snap : nullptr;
         p.mean = ctx->cfg.mean;
         p.lr = ctx->cfg.lr;
@@ -389,10 +392,41 @@ static int check_steps(cocod_ctx *ctx, int k)
     return COCOD_OK;
 }
 
+static int need_builtin_gradient(cocod_ctx *ctx)
+{
+    if (ctx->cfg.grad == COCOD_GRAD_EXTERNAL)
+        return fail(ctx, COCOD_ERR_INVALID, "this context has no built-in gradient: use cocod_external_step");
+    return COCOD_OK;
+}
+
+int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (!g || !aligned16(g)) return fail(ctx, COCOD_ERR_INVALID, "g must be a 16-byte aligned device pointer");
+    if (close_round && !ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_external_step: no round is open to close");
+    int rc = check_steps(ctx, 1);
+    if (rc != COCOD_OK) return rc;
+    if (close_round && !ctx->dry) {      // the mean is consumed inside this step
+        if (ctx->schedule != COCOD_SCHED_OVERLAP) {
+            rc = enqueue_mean(ctx, ctx->s_compute);
+            if (rc != COCOD_OK) return rc;
+        } else if (ctx->s_avg != ctx->s_compute) {
+            COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
+        }
+    }
+    rc = enqueue_step(ctx, close_round != 0, g);
+    if (rc == COCOD_OK && close_round) {
+        ctx->averaging = false;
+        ctx->snap = nullptr;
+    }
+    return rc;
+}
+
 int cocod_local_steps(cocod_ctx *ctx, int k)
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
     int rc = check_steps(ctx, k);
+    if (rc == COCOD_OK && k > 0) rc = need_builtin_gradient(ctx);
     for (int s = 0; s < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
     return rc;
 }
@@ -404,6 +438,8 @@ int cocod_local_steps_end_apply(cocod_ctx *ctx, int k)
     int rc = check_steps(ctx, k);
     if (rc != COCOD_OK) return rc;
     if (k == 0) return cocod_average_end_apply(ctx);
+    rc = need_builtin_gradient(ctx);
+    if (rc != COCOD_OK) return rc;
     if (ctx->cfg.grad == COCOD_GRAD_MLP) {      // the MLP step has no line-6 epilogue: separate kernel
         for (int s = 0; s < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
         return rc == COCOD_OK ? cocod_average_end_apply(ctx) : rc;
@@ -563,6 +599,21 @@ int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches
         launches[kind] += 1;
     }
     ctx->t_used = 0;
+    return COCOD_OK;
+}
+
+int cocod_consensus_distance(cocod_ctx *ctx, double *result)
+{
+    if (!ctx || !result) return fail(nullptr, COCOD_ERR_INVALID, "ctx and result must not be NULL");
+    *result = 0.0;
+    if (ctx->dry) return COCOD_OK;
+    const uint32_t n_chunks = static_cast<uint32_t>(ctx->chunks.size());
+    if (!ctx->d_reduce)
+        COCOD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->d_reduce), (static_cast<size_t>(n_chunks) + 1) * sizeof(double)));
+    COCOD_HIP(ctx, cocod::launch_consensus_distance(ctx->s_compute, ctx->d_chunks, n_chunks, ctx->live, ctx->cfg.stride,
+                                                    ctx->cfg.W, ctx->d_weights, ctx->d_reduce + 1, ctx->d_reduce));
+    COCOD_HIP(ctx, hipMemcpyAsync(result, ctx->d_reduce, sizeof(double), hipMemcpyDeviceToHost, ctx->s_compute));
+    COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
     return COCOD_OK;
 }
 

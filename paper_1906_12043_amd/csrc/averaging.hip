@@ -157,6 +157,69 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
     }
 }
 
+// ---- consensus distance: sum_i p_i || xbar - x_i ||^2 with xbar = sum_i p_i x_i ---------------------
+// (the quantity bounded by Lemma 2 of the paper).  A scalar, so this is where wave and LDS reductions
+// belong: per thread a column quad (two passes over the W rows, the second one from cache), then a
+// butterfly over the wave, the four wave sums through LDS, one double per block; a second one-block
+// kernel adds the block partials in a fixed order, so the result is deterministic.
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+    #pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <bool WEIGHTED>
+__global__ __launch_bounds__(kStepThreads) void consensus_partial_kernel(const Chunk *table, const float *x, uint64_t stride,
+                                                                         uint32_t W, const float *weights, double *partial)
+{
+    __shared__ double wave_part[kStepThreads / 64];
+    const Chunk ck = table[blockIdx.x];
+    const uint32_t e = threadIdx.x * 4;
+    double local = 0.0;
+    if (e < ck.n) {
+        const float *col = x + static_cast<uint64_t>(ck.mem_quad) * 4 + e;
+        const float uniform = 1.0f / static_cast<float>(W);
+        float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t i = 0; i < W; ++i) {
+            const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
+            const float pw = WEIGHTED ? weights[i] : uniform;
+            m.x += pw * r.x; m.y += pw * r.y; m.z += pw * r.z; m.w += pw * r.w;
+        }
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t i = 0; i < W; ++i) {
+            const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
+            const float pw = WEIGHTED ? weights[i] : uniform;
+            acc.x += pw * (r.x - m.x) * (r.x - m.x); acc.y += pw * (r.y - m.y) * (r.y - m.y);
+            acc.z += pw * (r.z - m.z) * (r.z - m.z); acc.w += pw * (r.w - m.w) * (r.w - m.w);
+        }
+        const uint32_t keep = ck.n - e;                   // alignment pads of a tensor's tail quad do not count
+        local = static_cast<double>(acc.x);
+        if (keep > 1) local += static_cast<double>(acc.y);
+        if (keep > 2) local += static_cast<double>(acc.z);
+        if (keep > 3) local += static_cast<double>(acc.w);
+    }
+    local = wave_sum_f64(local);
+    if (threadIdx.x % 64 == 0) wave_part[threadIdx.x / 64] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+        for (uint32_t w = 0; w < kStepThreads / 64; ++w) s += wave_part[w];
+        partial[blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void consensus_final_kernel(const double *partial, uint32_t n, double *out)
+{
+    __shared__ double wave_part[4];
+    double local = 0.0;
+    for (uint32_t i = threadIdx.x; i < n; i += 256) local += partial[i];
+    local = wave_sum_f64(local);
+    if (threadIdx.x % 64 == 0) wave_part[threadIdx.x / 64] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
+}
+
 inline uint32_t blocks_for(uint64_t n_quads) { return static_cast<uint32_t>((n_quads + kAvgThreads - 1) / kAvgThreads); }
 
 }  // namespace
@@ -200,6 +263,15 @@ hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, 
     }
     if (weights) hipLaunchKernelGGL((mean_correct_kernel<true, 0>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
     else         hipLaunchKernelGGL((mean_correct_kernel<false, 0>), grid, block, 0, stream, x, snap, stride, W, begin, n_quads, weights, mean);
+    return hipGetLastError();
+}
+
+hipError_t launch_consensus_distance(hipStream_t stream, const Chunk *table, uint32_t n_chunks, const float *x,
+                                     uint64_t stride, uint32_t W, const float *weights, double *partial, double *out)
+{
+    if (weights) hipLaunchKernelGGL((consensus_partial_kernel<true>), dim3(n_chunks), dim3(kStepThreads), 0, stream, table, x, stride, W, weights, partial);
+    else         hipLaunchKernelGGL((consensus_partial_kernel<false>), dim3(n_chunks), dim3(kStepThreads), 0, stream, table, x, stride, W, weights, partial);
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, stream, partial, n_chunks, out);
     return hipGetLastError();
 }
 

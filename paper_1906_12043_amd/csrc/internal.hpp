@@ -30,6 +30,7 @@ struct StepParams {
     float *v;            // momentum, unused when momentum == 0
     const float *h;
     const float *c;
+    const float *g;      // non-null: the stochastic gradient is read from here ([W][stride]) instead of h, c, noise
     const float *snap;   // non-null: this is the last step of a round and line 6 is applied to its result
     const float *mean;   //           x = mean + (x_new - snap); mean is [stride], valid when snap is set
     float lr, momentum, weight_decay, sigma;
@@ -54,6 +55,10 @@ hipError_t launch_correct(hipStream_t stream, float *x, const float *snap, const
 hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, uint64_t stride,
                                uint32_t W, uint64_t begin, uint64_t end, const float *weights,
                                float *mean);
+
+// out[0] = sum_i p_i || xbar - x_i ||^2 over the real (unpadded) elements; partial: n_chunks doubles of scratch
+hipError_t launch_consensus_distance(hipStream_t stream, const Chunk *table, uint32_t n_chunks, const float *x,
+                                     uint64_t stride, uint32_t W, const float *weights, double *partial, double *out);
 
 hipError_t launch_fill_quadratic(hipStream_t stream, const Chunk *table, uint32_t n_chunks, uint32_t W,
                                  uint64_t stride, uint64_t padded_d, float *h, float *c,

@@ -64,7 +64,10 @@ __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const S
 // TAIL: 0 = plain local step; 1 = last step of a round with line 6 applied to the fresh model
 // before it is stored, x = mean + ((x - gamma v) - snap); 2 = the same when the step reads the
 // stored models themselves (k = 1: snap is x_in, no extra read).
-template <bool HAS_V, bool NOISE, int TAIL>
+// GRAD: where the stochastic gradient G comes from.
+enum { kGradQuadNoisy = 0, kGradQuadExact = 1, kGradExternal = 2 };
+
+template <bool HAS_V, int GRAD, int TAIL>
 __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParams p)
 {
     const Chunk ck = p.table[blockIdx.x];
@@ -75,15 +78,19 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     const __amdgpu_buffer_rsrc_t rx_in = make_rsrc(p.x_in + row, bytes);
     const __amdgpu_buffer_rsrc_t rx_out = make_rsrc(p.x_out + row, bytes);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(HAS_V ? p.v + row : p.x_in + row, bytes);
-    const __amdgpu_buffer_rsrc_t rh = make_rsrc(p.h + row, bytes);
-    const __amdgpu_buffer_rsrc_t rc = make_rsrc(p.c + row, bytes);
 
     const uint32_t e = threadIdx.x * 4;                   // first element of this thread's quad
     const uint32_t off = e * 4;
     const f4 x0 = load_quad(rx_in, off);
     const f4 v0 = HAS_V ? load_quad(rv, off) : f4{0.f, 0.f, 0.f, 0.f};
-    const f4 h = load_quad(rh, off);
-    const f4 c = load_quad(rc, off);
+    f4 g;
+    if (GRAD == kGradExternal) {                          // caller's gradient: read x, v, g; write x, v (20 B)
+        g = load_quad(make_rsrc(p.g + row, bytes), off);
+    } else {
+        const f4 h = load_quad(make_rsrc(p.h + row, bytes), off);
+        const f4 c = load_quad(make_rsrc(p.c + row, bytes), off);
+        g = h * (x0 - c);
+    }
     f4 snap = x0, mean = f4{0.f, 0.f, 0.f, 0.f};
     if (TAIL == 1) snap = load_quad(make_rsrc(p.snap + row, bytes), off);
     if (TAIL != 0) {
@@ -92,8 +99,7 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
         mean = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rm, static_cast<int>(off), 0, 0));
     }
 
-    f4 g = h * (x0 - c);
-    if (NOISE)
+    if (GRAD == kGradQuadNoisy)
         g += p.sigma * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, static_cast<uint32_t>(ck.glob_off & 3u), p, worker);
     g += p.weight_decay * x0;
     f4 v = v0;
@@ -115,12 +121,20 @@ template <int TAIL>
 void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
     const dim3 grid(p.n_chunks, p.W), block(kStepThreads);
-    const bool has_v = p.momentum != 0.0f, noise = p.sigma != 0.0f;
+    const bool has_v = p.momentum != 0.0f;
+    const int grad = p.g ? kGradExternal : (p.sigma != 0.0f ? kGradQuadNoisy : kGradQuadExact);
     // start/stop (may be null) receive the kernel's own begin and end timestamps
-    if (has_v && noise)       hipExtLaunchKernelGGL((quad_step_kernel<true, true, TAIL>), grid, block, 0, stream, start, stop, 0, p);
-    else if (has_v && !noise) hipExtLaunchKernelGGL((quad_step_kernel<true, false, TAIL>), grid, block, 0, stream, start, stop, 0, p);
-    else if (noise)           hipExtLaunchKernelGGL((quad_step_kernel<false, true, TAIL>), grid, block, 0, stream, start, stop, 0, p);
-    else                      hipExtLaunchKernelGGL((quad_step_kernel<false, false, TAIL>), grid, block, 0, stream, start, stop, 0, p);
+#define COCOD_LAUNCH_STEP(V, G) hipExtLaunchKernelGGL((quad_step_kernel<V, G, TAIL>), grid, block, 0, stream, start, stop, 0, p)
+    if (has_v) {
+        if (grad == kGradExternal)       COCOD_LAUNCH_STEP(true, kGradExternal);
+        else if (grad == kGradQuadNoisy) COCOD_LAUNCH_STEP(true, kGradQuadNoisy);
+        else                             COCOD_LAUNCH_STEP(true, kGradQuadExact);
+    } else {
+        if (grad == kGradExternal)       COCOD_LAUNCH_STEP(false, kGradExternal);
+        else if (grad == kGradQuadNoisy) COCOD_LAUNCH_STEP(false, kGradQuadNoisy);
+        else                             COCOD_LAUNCH_STEP(false, kGradQuadExact);
+    }
+#undef COCOD_LAUNCH_STEP
 }
 
 }  // namespace

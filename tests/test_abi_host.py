@@ -209,3 +209,31 @@ def test_local_steps_end_apply_state_machine():
         assert e.value.status == P.ERR_INVALID and ctx.is_averaging()
         ctx.local_steps_end_apply(1)
         assert not ctx.is_averaging() and ctx.get_step() == 4
+
+
+def test_external_step_state_machine():
+    g = 0x70000000
+    with dry(grad=P.GRAD_EXTERNAL, h=None, c=None) as ctx:
+        for call in (lambda: ctx.local_steps(1), lambda: ctx.local_steps_end_apply(1)):
+            ctx.average_begin() if not ctx.is_averaging() else None
+            with pytest.raises(P.CocodError) as e:
+                call()
+            assert e.value.status == P.ERR_INVALID and "external" in str(e.value)
+        ctx.local_steps(0)                               # zero steps need no gradient
+        a = ctx.live_model()
+        ctx.external_step(g)
+        assert ctx.live_model() != a and ctx.get_step() == 1 and ctx.is_averaging()
+        ctx.external_step(g, close_round=True)
+        assert not ctx.is_averaging() and ctx.get_step() == 2
+        with pytest.raises(P.CocodError) as e:
+            ctx.external_step(g, close_round=True)
+        assert e.value.status == P.ERR_STATE
+        for bad in (None, g + 4):
+            with pytest.raises(P.CocodError) as e:
+                ctx.external_step(bad)
+            assert e.value.status == P.ERR_INVALID
+        ctx.external_step(g)                             # outside a round: plain SGD step
+        assert ctx.get_step() == 3
+    with dry() as ctx:                                   # also legal on a context with a built-in gradient
+        ctx.external_step(g)
+        assert ctx.get_step() == 1

@@ -221,3 +221,66 @@ def test_line6_inside_last_step_is_bit_identical_to_separate_kernels(k, packed):
     a.ctx.average_begin(); a.ctx.average_end_apply()
     assert np.array_equal(a.x(), b.x())
     a.close(); b.close()
+
+
+@pytest.mark.parametrize("packed,weights", [(False, None), (True, None), (False, [0.1, 0.2, 0.3, 0.15, 0.25])])
+def test_consensus_distance_and_local_sgd_schedule(packed, weights):
+    """The diagnostic of Lemma 2's quantity, and Local-SGD built from the same calls: k local steps,
+    then a round with zero local steps (every worker lands on the mean of the CURRENT models)."""
+    W, k = 5, 3
+    sizes = [7, 1024, 2050, 3, 1021] if packed else None
+    d = sum(sizes) if packed else 30_011
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=23, weights=weights)
+    h, c = synth_inputs.quadratic_data(14, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    assert g.ctx.consensus_distance() == 0.0
+    for r in range(3):
+        g.ctx.round(k); o.round(k)
+        got, want = g.ctx.consensus_distance(), o.consensus_distance()
+        assert want > 0 and abs(got - want) <= 1e-5 * want, (got, want)
+        assert g.ctx.consensus_distance() == got                         # deterministic reduction
+    for schedule in (P.SCHED_OVERLAP, P.SCHED_FUSED):                    # Local-SGD rounds
+        g.ctx.set_schedule(schedule)
+        g.ctx.local_steps(k); g.ctx.average_begin(); g.ctx.average_end_apply()
+        o.local_steps(k); o.average_begin(); o.average_end_apply()
+        check_state(g, o, what="local-sgd")
+        assert g.ctx.consensus_distance() <= 1e-9                        # fp32 mean of equal rows: last-bit noise only
+        x = g.x()
+        assert all(np.array_equal(x[0], x[i]) for i in range(1, W))
+    g.close()
+
+
+@pytest.mark.parametrize("packed,mu", [(False, 0.9), (True, 0.9), (False, 0.0)])
+def test_external_gradient_steps(packed, mu):
+    """The caller supplies G: here the oracle's own logged gradients (oracle -> device), so the device
+    must reproduce the oracle's trajectory through cocod_external_step."""
+    W, k, rounds = 3, 3, 3
+    sizes = [7, 1024, 2050, 3, 1021] if packed else None
+    d = sum(sizes) if packed else 5003
+    hyper = dict(lr=0.05, momentum=mu, weight_decay=5e-4, seed=17)
+    h, c = synth_inputs.quadratic_data(13, W, d)
+    o = orc.QuadraticOracle(h, c, noise_sigma=0.01, **hyper)
+    g = GpuWorkers(W, d, tensor_numel=sizes, grad=P.GRAD_EXTERNAL, **hyper)
+    with pytest.raises(P.CocodError) as e:
+        g.ctx.local_steps(1)                                  # no built-in gradient in this context
+    assert e.value.status == P.ERR_INVALID
+    with pytest.raises(P.CocodError) as e:
+        g.ctx.external_step(g.h, close_round=True)            # no round open
+    assert e.value.status == P.ERR_STATE
+    for r in range(rounds):
+        g.ctx.average_begin(); o.average_begin()
+        for s in range(k):
+            G = o.local_steps(1, log_gradients=True)[0]
+            g.ctx.sync()                                      # the previous step has consumed the buffer
+            gbuf = g._upload(G.astype(np.float32))
+            torch.cuda.synchronize()
+            last = s == k - 1 and r % 2 == 0                  # alternate: line 6 inside the step / separate
+            g.ctx.external_step(gbuf, close_round=last)
+        if r % 2 == 1:
+            g.ctx.average_end_apply()
+        o.average_end_apply()
+        assert not g.ctx.is_averaging()
+        check_state(g, o, what="external round %d" % r)
+    assert g.ctx.get_step() == o.step
+    g.close()

@@ -279,3 +279,22 @@ def test_step_counter_is_global_across_rounds():
     o.average_begin(); o.local_steps(1)
     z = np.stack([orc.normals(4, orc.TAG_NOISE, i, 2, 0, n) for i in range(W)])
     assert np.allclose(o.x, before - z, rtol=0, atol=1e-15)
+
+
+def test_consensus_distance():
+    """The left-hand quantity of Lemma 2 for one t: hand value, the variance identity
+    sum p ||x - xbar||^2 = sum p ||x||^2 - ||xbar||^2, zero at consensus, reset by averaging."""
+    h = np.ones((2, 1), np.float32); c = np.zeros((2, 1), np.float32)
+    o = orc.QuadraticOracle(h, c, np.array([[0.0], [2.0]]), lr=0.1)
+    assert o.consensus_distance() == 1.0                       # mean 1, both workers at distance 1
+    ow = orc.QuadraticOracle(h, c, np.array([[0.0], [2.0]]), lr=0.1, weights=[0.25, 0.75])
+    assert abs(ow.consensus_distance() - (0.25 * 1.5**2 + 0.75 * 0.5**2)) < 1e-15
+    big = make(8, 200, **HYPER)
+    assert big.consensus_distance() == 0.0                     # all workers start equal
+    big.round(3); big.round(3)
+    x = big.x
+    want = np.mean(np.sum(x * x, axis=1)) - np.sum(x.mean(axis=0) ** 2)
+    assert abs(big.consensus_distance() - want) < 1e-12 and big.consensus_distance() > 0
+    # Local-SGD style averaging (a round with zero local steps) brings every worker to the mean
+    big.average_begin(); big.average_end_apply()
+    assert big.consensus_distance() < 1e-28
