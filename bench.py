@@ -24,7 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
-STEP_BYTES = 24                 # plain local step: read x, v, h, c; write x, v (fp32)
+STEP_BYTES = 24                 # plain local step: read x, v, h, c; write x, v (fp32); 16 without momentum
 # HBM bytes per launch of the plain step kernel at this workload from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999, factors from the known-size copy kernel):
 # profiles/kernels_C2_W16_d11.2M_hbm_counters.md
@@ -78,6 +78,41 @@ def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
                 avg[i] = total_ms / n / 1e3
         ctx.step_timing(0)
     return elapsed / rounds, avg[0], avg[1]
+
+
+def timelines(ctx, torch, P, k, rounds):
+    """The four timelines that the paper's time-speedup analysis compares, built from the same
+    kernels on one GPU, as average milliseconds per local step (the paper's T_N^av up to the factor N):
+      s_sgd      one step, then blocking average of the models          (communicate every step, sequential)
+      local_sgd  k steps, then blocking average                         (communicate every k steps, sequential)
+      cocod      the round with the mean overlapped and line 6 separate (every k steps, in parallel)
+      cocod_fused_tail  the same with line 6 inside the last step
+    Blocking average = a round with zero local steps: every worker lands on the mean of the current models."""
+    def timed(body, steps_per_iter):
+        for _ in range(2):
+            body()
+        ctx.sync()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            body()
+        ctx.sync()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / rounds / steps_per_iter * 1e3
+
+    def blocking_average():
+        ctx.average_begin()
+        ctx.average_end_apply()
+
+    out = {}
+    ctx.set_schedule(P.SCHED_FUSED)       # nothing to overlap with: mean and broadcast in one kernel
+    out["s_sgd"] = timed(lambda: (ctx.local_steps(1), blocking_average()), 1)
+    out["local_sgd"] = timed(lambda: (ctx.local_steps(k), blocking_average()), k)
+    ctx.set_schedule(P.SCHED_OVERLAP)
+    out["cocod"] = timed(lambda: ctx.round(k), k)
+    out["cocod_fused_tail"] = timed(lambda: ctx.round_fused_tail(k), k)
+    out["k"] = k
+    return out
 
 
 def cpu_baseline(cfg, k):
@@ -156,8 +191,9 @@ def bench_mlp(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", choices=("C2", "C4"), default="C2",
-                    help="C2: the headline quadratic workload; C4: the MLP-gradient workers")
+    ap.add_argument("--workload", choices=("C1", "C2", "C3", "C4", "C5"), default="C2",
+                    help="C2: the headline workload (ResNet18-sized, W=16); C1 tiny, C3 VGG16-sized, C5 bucketed "
+                         "tensor list with W=64 (same quadratic path); C4: the MLP-gradient workers")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50, help="timed rounds")
     ap.add_argument("--warmup", type=int, default=5)
@@ -183,13 +219,21 @@ def main():
     if args.workload == "C4":
         return bench_mlp(args)
 
-    cfg = synth_inputs.CONFIGS["C2_resnet18"]
+    names = {"C1": "C1_tiny", "C2": "C2_resnet18", "C3": "C3_vgg16", "C5": "C5_bucketed"}
+    labels = {"C1": "C1 tiny flat vector", "C2": "C2 ResNet18-sized flat vector", "C3": "C3 ImageNet-VGG16-sized flat vector",
+              "C5": "C5 ResNet18-like list of 62 tensors in 25 MiB buckets"}
+    cfg = synth_inputs.CONFIGS[names[args.workload]]
     W, d = cfg["W"], cfg["d"]
+    sizes = (synth_inputs.tensor_sizes(cfg["seed"], cfg["n_tensors"], d, cfg["tensor_lo"], cfg["tensor_hi"])
+             if "n_tensors" in cfg else None)
+    if args.k not in cfg["k"] and args.workload != "C2":
+        args.k = cfg["k"][0]
     dev = torch.device("cuda:0")
-    stride, _, _ = P.plan_layout(d)
+    stride, _, _ = P.plan_layout(d, sizes, cfg.get("bucket_bytes", 0))
+    stride = (stride + 1023) // 1024 * 1024     # worker rows start on 4 KiB boundaries (measured: faster streaming)
     xA = torch.zeros((W, stride), device=dev)
     xB = torch.zeros((W, stride), device=dev)
-    v = torch.zeros((W, stride), device=dev)
+    v = torch.zeros((W, stride), device=dev) if cfg["momentum"] else None
     mean = torch.zeros(stride, device=dev)
     h = torch.empty((W, stride), device=dev)
     c = torch.empty((W, stride), device=dev)
@@ -197,22 +241,28 @@ def main():
     torch.cuda.synchronize()
     ctx = P.Context(W=W, d=d, stride=stride, xA=xA, xB=xB, v=v, mean=mean, h=h, c=c, lr=cfg["lr"],
                     momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], noise_sigma=cfg["noise_sigma"],
-                    seed=cfg["seed"], compute_stream=s_compute, avg_stream=s_avg)
+                    seed=cfg["seed"], tensor_numel=sizes, bucket_bytes=cfg.get("bucket_bytes", 0),
+                    compute_stream=s_compute, avg_stream=s_avg)
     ctx.fill_quadratic()
     ctx.sync()
 
+    global STEP_BYTES
+    if not cfg["momentum"]:
+        STEP_BYTES = 16
+    traffic = STEP_TRAFFIC_BYTES if args.workload == "C2" else None
     k, variant = args.k, args.variant
     per_round, plain_s, tail_s = time_rounds(ctx, torch, k, args.steps, args.warmup, variant)
     out = {
-        "metric": "worker-param-updates/s per CoCoD round (W=16, d=11.2M)",
+        "metric": "worker-param-updates/s per CoCoD round (W=%d, d=%.4gM)" % (W, d / 1e6),
         "value": W * d * k / per_round,
         "unit": "worker-param-updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": per_round * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "C2 ResNet18-sized flat vector: W=16 workers x d=11.2M fp32, quadratic+Philox-noise "
-                               "gradient, momentum 0.9, wd 5e-4, lr 0.05", "k": k, "variant": variant,
+        "config": {"workload": "%s: W=%d workers x d=%d fp32, quadratic+Philox-noise gradient, momentum %g, wd %g, lr %g"
+                               % (labels[args.workload], W, d, cfg["momentum"], cfg["weight_decay"], cfg["lr"]),
+                   "k": k, "variant": variant,
                    "schedule": "overlap (2 streams)", "W": W, "d": d},
         "round_model_GBps": model_round_bytes(W, d, k) / per_round / 1e9,
         "round_moved_GBps": moved_round_bytes(W, d, k, variant) / per_round / 1e9,
@@ -221,7 +271,7 @@ def main():
     if plain_s:
         n_plain = args.steps * (k if variant == "separate" else k - 1)
         out["roofline"] = roofline("quad_step_kernel<momentum, noise, plain>", STEP_BYTES * W * d, plain_s, n_plain,
-                                   STEP_TRAFFIC_BYTES)
+                                   traffic)
     if tail_s:
         tail = roofline("quad_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k), tail_s, args.steps, None)
         out["roofline_tail" if plain_s else "roofline"] = tail
@@ -244,10 +294,11 @@ def main():
             pr, _, _ = time_rounds(ctx, torch, k, args.steps, 2, "separate", False)
             sched[name] = pr * 1e3
         out["separate_schedule_ms_per_round"] = sched
+        out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, args.steps)
     ctx.close()
     del xA, xB, v, mean, h, c
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == "C2":
         out["cpu_baseline"] = cpu_baseline(cfg, k)
     print(json.dumps(out))
     return 0

@@ -75,9 +75,13 @@ enum {
  * Memory layout.  Every per-worker array is worker-major: element e of worker i
  * lives at base[i * stride + e], 0 <= e < padded_d.  A flat model (n_tensors <= 1)
  * has padded_d = d rounded up to 4.  A parameter list of n_tensors tensors is
- * packed in list order, each tensor starting on a 16-byte boundary (offset
- * multiple of 4 elements); see cocod_plan_layout.  Pad elements are carried
- * along by the averaging kernels and never influence real elements.
+ * packed in list order, each tensor starting on a 4 KiB boundary (offset multiple
+ * of 1024 elements) and the end of the list rounded up to 4; see
+ * cocod_plan_layout.  The elements in the gaps are pads: the local step never
+ * touches them, the averaging kernels carry them along, and they never
+ * influence real elements (their contents are unspecified).  For full memory
+ * bandwidth choose stride as a multiple of 1024 elements, so that every
+ * worker's row starts on a 4 KiB boundary as well (any multiple of 4 is legal).
  */
 typedef struct cocod_config {
     uint32_t struct_size;          /* sizeof(cocod_config); checked */

@@ -19,8 +19,9 @@
 //
 // The generator's 128-bit block is keyed by the UNPADDED global parameter index, so
 // results do not depend on how tensors are packed; when a tensor starts at a global
-// index that is not a multiple of 4, a thread's quad straddles two generator blocks
-// (block-uniform case, second block computed only then).
+// index that is not a multiple of 4, a thread's memory quad straddles two generator blocks.
+// Threads own consecutive blocks, so the missing normals are the right-hand neighbour's: three
+// cross-lane moves (one LDS word across a wave boundary) instead of a second generator call.
 #include "internal.hpp"
 #include "philox.hpp"
 
@@ -48,17 +49,34 @@ __device__ __forceinline__ void store_quad(__amdgpu_buffer_rsrc_t r, uint32_t by
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, a), r, static_cast<int>(byte_off), 0, kAuxNonTemporal);
 }
 
-// Four normals for the thread's quad whose first element has global index 4*q + shift.
+// Four normals for a thread's memory quad whose first element has global index 4*q + shift.
+// shift == 0: the quad is one generator block.  Otherwise the quad takes the last 4 - shift normals
+// of block q and the first `shift` normals of block q + 1.  Threads own consecutive blocks, so block
+// q + 1 is the right-hand neighbour's own block: a cross-lane move inside a wave, a word of LDS
+// across a wave boundary, and one extra generator call by the block's very last thread.
+// Must be called by all threads of the block (it synchronises when shift != 0).
 __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const StepParams &p, uint32_t worker)
 {
     const Normals4 a = box_muller_fast(
         philox4x32_10(static_cast<uint32_t>(q), p.step, worker, kTagNoise, p.key0, p.key1));
     if (shift == 0) return f4{a.z[0], a.z[1], a.z[2], a.z[3]};          // block-uniform branch
-    const Normals4 b = box_muller_fast(
-        philox4x32_10(static_cast<uint32_t>(q + 1), p.step, worker, kTagNoise, p.key0, p.key1));
-    if (shift == 1) return f4{a.z[1], a.z[2], a.z[3], b.z[0]};
-    if (shift == 2) return f4{a.z[2], a.z[3], b.z[0], b.z[1]};
-    return f4{a.z[3], b.z[0], b.z[1], b.z[2]};
+    __shared__ float first_of_wave[kStepThreads / 64][3];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    if (lane == 0) { first_of_wave[wave][0] = a.z[0]; first_of_wave[wave][1] = a.z[1]; first_of_wave[wave][2] = a.z[2]; }
+    __syncthreads();
+    float b0 = __shfl_down(a.z[0], 1, 64), b1 = __shfl_down(a.z[1], 1, 64), b2 = __shfl_down(a.z[2], 1, 64);
+    if (lane == 63u) {
+        if (wave + 1 < kStepThreads / 64) {
+            b0 = first_of_wave[wave + 1][0]; b1 = first_of_wave[wave + 1][1]; b2 = first_of_wave[wave + 1][2];
+        } else {                                                        // one lane of one wave per block
+            const Normals4 nb = box_muller_fast(
+                philox4x32_10(static_cast<uint32_t>(q + 1), p.step, worker, kTagNoise, p.key0, p.key1));
+            b0 = nb.z[0]; b1 = nb.z[1]; b2 = nb.z[2];
+        }
+    }
+    if (shift == 1) return f4{a.z[1], a.z[2], a.z[3], b0};
+    if (shift == 2) return f4{a.z[2], a.z[3], b0, b1};
+    return f4{a.z[3], b0, b1, b2};
 }
 
 // TAIL: 0 = plain local step; 1 = last step of a round with line 6 applied to the fresh model
@@ -79,6 +97,7 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     const __amdgpu_buffer_rsrc_t rx_out = make_rsrc(p.x_out + row, bytes);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(HAS_V ? p.v + row : p.x_in + row, bytes);
 
+    const uint32_t shift = static_cast<uint32_t>(ck.glob_off & 3u);
     const uint32_t e = threadIdx.x * 4;                   // first element of this thread's quad
     const uint32_t off = e * 4;
     const f4 x0 = load_quad(rx_in, off);
@@ -100,7 +119,7 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     }
 
     if (GRAD == kGradQuadNoisy)
-        g += p.sigma * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, static_cast<uint32_t>(ck.glob_off & 3u), p, worker);
+        g += p.sigma * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, shift, p, worker);
     g += p.weight_decay * x0;
     f4 v = v0;
     if (HAS_V) { v = p.momentum * v0 + g; g = v; }

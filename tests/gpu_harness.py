@@ -8,15 +8,16 @@ import paper_1906_12043_amd as P
 
 def packed_positions(tensor_numel, d):
     """Memory element offset (inside a worker row) of every global parameter index 0..d-1,
-    computed independently of the library: tensors in order, each start rounded up to 4."""
+    computed independently of the library: tensors in order, each start rounded up to 1024."""
     if not tensor_numel:
         return np.arange(d, dtype=np.int64)
     pos = np.empty(d, dtype=np.int64)
     at = g = 0
     for n in tensor_numel:
+        at = (at + 1023) // 1024 * 1024
         pos[g:g + n] = np.arange(at, at + n)
         g += n
-        at = (at + n + 3) // 4 * 4
+        at += n
     return pos
 
 

@@ -44,10 +44,13 @@ def test_config_struct_matches_header_size():
 # ---- layout --------------------------------------------------------------------------------
 
 def expected_layout(sizes, bucket_bytes):
+    """Tensors start on 1024-element (4 KiB) boundaries; the list's end is rounded up to 4 elements."""
     offsets, at = [], 0
     for n in sizes:
+        at = (at + 1023) // 1024 * 1024
         offsets.append(at)
-        at = (at + n + 3) // 4 * 4
+        at += n
+    at = (at + 3) // 4 * 4
     cap = bucket_bytes // 4
     begins, start = [0], 0
     for t in range(1, len(sizes)):
@@ -71,7 +74,7 @@ def test_plan_layout_bucketed_config():
     got = P.plan_layout(cfg["d"], sizes, cfg["bucket_bytes"])
     assert got == expected_layout(sizes, cfg["bucket_bytes"])
     padded, offsets, begins = got
-    assert all(o % 4 == 0 for o in offsets) and padded % 4 == 0 and padded - cfg["d"] <= 3 * 62
+    assert all(o % 1024 == 0 for o in offsets) and padded % 4 == 0 and padded - cfg["d"] <= 1023 * 61 + 3
     assert len(begins) - 1 >= 2                    # 44.8 MB of parameters in buckets of 25 MiB
     for a, b in zip(begins, begins[1:]):
         assert a in offsets and b > a
@@ -176,9 +179,9 @@ def test_plan_of_context():
     with dry(d=10000) as ctx:
         assert ctx.get_plan() == (10000, 10, 1)     # 9 x 1024 + 784
     sizes = [5000, 3, 4097]
-    with dry(d=sum(sizes), tensor_numel=sizes, stride=9112, bucket_bytes=20480) as ctx:
+    with dry(d=sum(sizes), tensor_numel=sizes, stride=10244, bucket_bytes=20480) as ctx:
         padded, chunks, buckets = ctx.get_plan()
-        assert padded == 5000 + 4 + 4100 and chunks == 5 + 1 + 5 and buckets == 2
+        assert padded == 5120 + 1024 + 4100 and chunks == 5 + 1 + 5 and buckets == 3
 
 
 def test_null_context_is_an_error_not_a_crash():
