@@ -69,6 +69,10 @@ int hip_fail(cocod_ctx *ctx, hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);         \
     } while (0)
 
+// A mean vector up to this size is expected to stay in the 256 MB last-level cache while the W
+// workers of a line-6 step read it one after the other.
+constexpr uint64_t kMeanCacheBytes = 128ull << 20;
+
 inline uint64_t round_up4(uint64_t n) { return (n + 3u) & ~static_cast<uint64_t>(3u); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -261,7 +265,10 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         }
         global += ctx->tensor_numel[t];
     }
-    if (ctx->chunks.size() > 0x7fffffffull) { delete ctx; return fail(nullptr, COCOD_ERR_INVALID, "too many chunks"); }
+    if (ctx->chunks.size() * static_cast<uint64_t>(cfg->W) > 0x7fffffffull) {   // one block per (chunk, worker)
+        delete ctx;
+        return fail(nullptr, COCOD_ERR_INVALID, "W * d is too large for one launch (more than 2^31 chunks of 1024 elements)");
+    }
 
     std::vector<float> weights;
     if (cfg->weights) weights.assign(cfg->weights, cfg->weights + cfg->W);
@@ -373,6 +380,7 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const float *g_ext = nu
         p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->step);
+        p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes ? 1u : 0u;
         hipEvent_t t0 = nullptr, t1 = nullptr;
         if (ctx->timing && ctx->t_used < ctx->t_start.size()) {
             t0 = ctx->t_start[ctx->t_used];

@@ -36,6 +36,7 @@ struct StepParams {
     float lr, momentum, weight_decay, sigma;
     uint32_t key0, key1; // generator key (seed low, seed high)
     uint32_t step;       // global step counter t
+    uint32_t worker_fastest;   // line-6 step only: order blocks worker-fastest (mean larger than the cache)
 };
 
 // start / stop: optional events that receive the kernel's own begin / end timestamps

@@ -29,7 +29,7 @@ def edge_columns(d, starts=()):
     return edges
 
 
-def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, stable_rounds=None):
+def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, stable_rounds=None, fused_tail=False):
     """Runs cfg["rounds"] rounds on the GPU (full size) and in the oracle (sampled columns).
 
     stable_rounds: for an iteration whose round map is expanding (see the k = 8 case below) the
@@ -46,7 +46,10 @@ def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, s
     o = orc.QuadraticOracle(h, c, idx=cols, **hyper_of(cfg))
     mirror = orc.QuadraticOracle(h, c, idx=cols, kind="f32", **hyper_of(cfg)) if stable_rounds else None
     for r in range(cfg["rounds"]):
-        g.ctx.round(k)
+        if fused_tail:
+            g.ctx.round_fused_tail(k)          # line 6 inside the last local step (the benchmark's variant)
+        else:
+            g.ctx.round(k)
         o.round(k)
         if mirror is not None:
             mirror.round(k)
@@ -83,18 +86,26 @@ def test_resnet18_size_fifty_rounds_sampled(k):
     subset_parity(synth_inputs.CONFIGS["C2_resnet18"], k)
 
 
-def test_vgg16_size_twenty_rounds_sampled():
-    subset_parity(synth_inputs.CONFIGS["C3_vgg16"], 2)
+@pytest.mark.parametrize("fused_tail", [False, True])
+def test_vgg16_size_twenty_rounds_sampled(fused_tail):
+    # with line 6 inside the last step this size also takes the worker-fastest block order (mean > cache)
+    subset_parity(synth_inputs.CONFIGS["C3_vgg16"], 2, fused_tail=fused_tail)
+
+
+@pytest.mark.parametrize("k", [1, 2])
+def test_resnet18_size_fifty_rounds_sampled_line6_in_last_step(k):
+    subset_parity(synth_inputs.CONFIGS["C2_resnet18"], k, fused_tail=True)
 
 
 def bucketed_sizes(cfg):
     return synth_inputs.tensor_sizes(cfg["seed"], cfg["n_tensors"], cfg["d"], cfg["tensor_lo"], cfg["tensor_hi"])
 
 
-@pytest.mark.parametrize("k", [1, 2, 4])
-def test_bucketed_tensor_list_sampled(k):
+@pytest.mark.parametrize("k,fused_tail", [(1, False), (2, False), (4, False), (2, True)])
+def test_bucketed_tensor_list_sampled(k, fused_tail):
     cfg = synth_inputs.CONFIGS["C5_bucketed"]
-    subset_parity(cfg, k, n_random=50_000, tensor_numel=bucketed_sizes(cfg), bucket_bytes=cfg["bucket_bytes"])
+    subset_parity(cfg, k, n_random=50_000, tensor_numel=bucketed_sizes(cfg), bucket_bytes=cfg["bucket_bytes"],
+                  fused_tail=fused_tail)
 
 
 def test_bucketed_tensor_list_sampled_k8_expanding_round_map():
