@@ -136,9 +136,10 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
     float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
     #pragma unroll
     for (int i = 0; i < R; ++i) {                          // same order and operations as column_mean
-        if (static_cast<uint32_t>(i) >= W) break;
-        const float pw = WEIGHTED ? weights[i] : 1.0f;
-        m.x += pw * s[i].x; m.y += pw * s[i].y; m.z += pw * s[i].z; m.w += pw * s[i].w;
+        if (static_cast<uint32_t>(i) < W) {                // guard, not break: the loop must unroll fully or s[] goes to scratch
+            const float pw = WEIGHTED ? weights[i] : 1.0f;
+            m.x += pw * s[i].x; m.y += pw * s[i].y; m.z += pw * s[i].z; m.w += pw * s[i].w;
+        }
     }
     if (!WEIGHTED) {
         const float inv = 1.0f / static_cast<float>(W);
@@ -147,13 +148,14 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
     st4(mean + e, m);
     #pragma unroll
     for (int i = 0; i < R; ++i) {
-        if (static_cast<uint32_t>(i) >= W) break;
-        float *xp = x + e + static_cast<uint64_t>(i) * stride;
-        const float4 xr = ld4_stream(xp);
-        float4 o;
-        o.x = m.x + (xr.x - s[i].x); o.y = m.y + (xr.y - s[i].y);
-        o.z = m.z + (xr.z - s[i].z); o.w = m.w + (xr.w - s[i].w);
-        st4_stream(xp, o);
+        if (static_cast<uint32_t>(i) < W) {
+            float *xp = x + e + static_cast<uint64_t>(i) * stride;
+            const float4 xr = ld4_stream(xp);
+            float4 o;
+            o.x = m.x + (xr.x - s[i].x); o.y = m.y + (xr.y - s[i].y);
+            o.z = m.z + (xr.z - s[i].z); o.w = m.w + (xr.w - s[i].w);
+            st4_stream(xp, o);
+        }
     }
 }
 

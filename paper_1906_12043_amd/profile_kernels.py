@@ -47,6 +47,13 @@ def main(reps=5):
     for _ in range(reps):
         ctx.round(1)
     ctx.sync()
+    ctx.set_schedule(P.SCHED_SERIAL)            # line 6 inside the last step: mean, plain step, step with line 6
+    for _ in range(reps):
+        ctx.round_fused_tail(2)
+    ctx.sync()
+    for _ in range(reps):                       # k = 1: the step with line 6 reads the stored models as its input
+        ctx.round_fused_tail(1)
+    ctx.sync()
     ctx.close()
     print("profile_kernels: done, W=%d d=%d stride=%d reps=%d" % (W, d, stride, reps))
 
