@@ -29,6 +29,8 @@ STEP_BYTES = 24                 # plain local step: read x, v, h, c; write x, v 
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999, factors from the known-size copy kernel):
 # profiles/kernels_C2_W16_d11.2M_hbm_counters.md
 STEP_TRAFFIC_BYTES = 4.3038e9
+# the same for the step that carries line 6 (it fetches the mean once per worker at the L2 boundary)
+TAIL_TRAFFIC_BYTES = {1: 5.0400e9, 2: 5.7568e9}     # k = 1 / k >= 2
 
 
 def model_round_bytes(W, d, k):
@@ -268,13 +270,24 @@ def main():
         "round_moved_GBps": moved_round_bytes(W, d, k, variant) / per_round / 1e9,
         "round_moved_frac_of_hbm_peak": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / HBM_PEAK_GBS,
     }
+    # "roofline" is the kernel with the largest share of the round's GPU time: with line 6 inside the
+    # last step that is this last step (it moves more bytes than a plain step); the plain step rides
+    # along as "roofline_plain_step" (at k = 2 it always shares the memory system with the mean).
+    plain = tail = None
     if plain_s:
         n_plain = args.steps * (k if variant == "separate" else k - 1)
-        out["roofline"] = roofline("quad_step_kernel<momentum, noise, plain>", STEP_BYTES * W * d, plain_s, n_plain,
-                                   traffic)
+        plain = roofline("quad_step_kernel<momentum, noise, plain>", STEP_BYTES * W * d, plain_s, n_plain, traffic)
     if tail_s:
-        tail = roofline("quad_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k), tail_s, args.steps, None)
-        out["roofline_tail" if plain_s else "roofline"] = tail
+        tail_traffic = TAIL_TRAFFIC_BYTES[min(k, 2)] if args.workload == "C2" else None
+        tail = roofline("quad_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k), tail_s, args.steps, tail_traffic)
+    if tail and (not plain or tail_s >= plain_s * (k - 1)):
+        out["roofline"] = tail
+        if plain:
+            out["roofline_plain_step"] = plain
+    else:
+        out["roofline"] = plain
+        if tail:
+            out["roofline_line6_step"] = tail
     if not args.headline_only:
         variants = {}
         for name in ("separate", "fused_tail"):
