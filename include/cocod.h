@@ -187,6 +187,15 @@ int cocod_local_steps_end_apply(cocod_ctx *ctx, int k);
  */
 int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round);
 
+/*
+ * The same step of Step II with g stored as 16-bit brain floats (the upper 16 bits of an fp32, as
+ * mixed-precision training produces): g is [W][stride] 16-bit elements, element (i, j) at
+ * g[i * stride + j], device memory, 8-byte aligned.  Each value is widened exactly to fp32 and the
+ * step then proceeds as cocod_external_step does.  18 bytes per parameter.  Same state rules and
+ * error behaviour.
+ */
+int cocod_external_step_bf16(cocod_ctx *ctx, const uint16_t *g, int close_round);
+
 /* Choose how Step I is scheduled; only legal while IDLE.  Default COCOD_SCHED_OVERLAP. */
 int cocod_set_schedule(cocod_ctx *ctx, int schedule);
 

@@ -140,6 +140,16 @@ class QuadraticOracle:
                 logged.append(g)
         return logged
 
+    def external_step(self, G):
+        """One iteration of Step II with a given stochastic gradient G [W][n] (a real model's
+        backward pass in the paper's experiments): g = G + wd x; v = mu v + g; x = x - lr v."""
+        g = np.asarray(G, dtype=self.real) + self.real(self.wd) * self.x
+        if self.v is not None:
+            self.v[...] = self.real(self.momentum) * self.v + g
+            g = self.v
+        self.x[...] = self.x - self.real(self.lr) * g
+        self.step += 1
+
     def average_begin(self):
         """Step I: store the models and take their (weighted) mean."""
         assert not self.averaging

@@ -64,6 +64,7 @@ def lib():
             "cocod_local_steps": ([vp, i32], i32),
             "cocod_local_steps_end_apply": ([vp, i32], i32),
             "cocod_external_step": ([vp, vp, i32], i32),
+            "cocod_external_step_bf16": ([vp, vp, i32], i32),
             "cocod_average_begin": ([vp], i32),
             "cocod_average_end_apply": ([vp], i32),
             "cocod_set_schedule": ([vp, i32], i32),
@@ -209,6 +210,9 @@ class Context:
 
     def external_step(self, g, close_round=False):
         return _check(lib().cocod_external_step(self.handle, _addr(g), int(close_round)), self.handle)
+
+    def external_step_bf16(self, g, close_round=False):
+        return _check(lib().cocod_external_step_bf16(self.handle, _addr(g), int(close_round)), self.handle)
 
     def round_fused_tail(self, k):
         """One round with line 6 applied inside the last local step."""

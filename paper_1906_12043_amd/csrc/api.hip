@@ -332,7 +332,7 @@ int cocod_sync(cocod_ctx *ctx)
 }
 
 // One local step on the compute stream; with_line6 fuses line 6 into it (last step of a round).
-static int enqueue_step(cocod_ctx *ctx, bool with_line6, const float *g_ext = nullptr)
+static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nullptr, bool g_bf16 = false)
 {
     // Keep the stored models intact: the first step of an open round reads them and
     // writes the spare buffer, which then becomes the live one.
@@ -370,7 +370,8 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const float *g_ext = nu
         p.v = ctx->cfg.v;
         p.h = ctx->cfg.h;
         p.c = ctx->cfg.c;
-        p.g = g_ext;
+        p.g = static_cast<const float *>(g_ext);
+        p.g_bf16 = g_bf16 ? 1u : 0u;
         p.snap = with_line6 ? ctx->snap : nullptr;
         p.mean = ctx->cfg.mean;
         p.lr = ctx->cfg.lr;
@@ -414,10 +415,11 @@ static int need_builtin_gradient(cocod_ctx *ctx)
     return COCOD_OK;
 }
 
-int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round)
+static int external_step(cocod_ctx *ctx, const void *g, bool bf16, int close_round)
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
-    if (!g || !aligned16(g)) return fail(ctx, COCOD_ERR_INVALID, "g must be a 16-byte aligned device pointer");
+    if (!g || (bf16 ? reinterpret_cast<uintptr_t>(g) % 8 != 0 : !aligned16(g)))
+        return fail(ctx, COCOD_ERR_INVALID, "g must be a device pointer aligned to %d bytes", bf16 ? 8 : 16);
     if (close_round && !ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_external_step: no round is open to close");
     int rc = check_steps(ctx, 1);
     if (rc != COCOD_OK) return rc;
@@ -429,12 +431,22 @@ int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round)
             COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
         }
     }
-    rc = enqueue_step(ctx, close_round != 0, g);
+    rc = enqueue_step(ctx, close_round != 0, g, bf16);
     if (rc == COCOD_OK && close_round) {
         ctx->averaging = false;
         ctx->snap = nullptr;
     }
     return rc;
+}
+
+int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round)
+{
+    return external_step(ctx, g, false, close_round);
+}
+
+int cocod_external_step_bf16(cocod_ctx *ctx, const uint16_t *g, int close_round)
+{
+    return external_step(ctx, g, true, close_round);
 }
 
 int cocod_local_steps(cocod_ctx *ctx, int k)

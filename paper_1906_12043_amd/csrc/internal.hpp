@@ -31,6 +31,7 @@ struct StepParams {
     const float *h;
     const float *c;
     const float *g;      // non-null: the stochastic gradient is read from here ([W][stride]) instead of h, c, noise
+    uint32_t g_bf16;     // g holds 16-bit brain floats (same element layout, half the bytes)
     const float *snap;   // non-null: this is the last step of a round and line 6 is applied to its result
     const float *mean;   //           x = mean + (x_new - snap); mean is [stride], valid when snap is set
     float lr, momentum, weight_decay, sigma;

@@ -32,6 +32,7 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAuxNonTemporal = 2;   // cache-policy bits of the buffer instructions: nt
 
@@ -83,7 +84,7 @@ __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const S
 // before it is stored, x = mean + ((x - gamma v) - snap); 2 = the same when the step reads the
 // stored models themselves (k = 1: snap is x_in, no extra read).
 // GRAD: where the stochastic gradient G comes from.
-enum { kGradQuadNoisy = 0, kGradQuadExact = 1, kGradExternal = 2 };
+enum { kGradQuadNoisy = 0, kGradQuadExact = 1, kGradExternal = 2, kGradExternalBf16 = 3 };
 
 template <bool HAS_V, int GRAD, int TAIL>
 __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParams p)
@@ -112,6 +113,13 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     f4 g;
     if (GRAD == kGradExternal) {                          // caller's gradient: read x, v, g; write x, v (20 B)
         g = load_quad(make_rsrc(p.g + row, bytes), off);
+    } else if (GRAD == kGradExternalBf16) {               // the same with 16-bit gradients (18 B): a brain float
+        const uint16_t *gb = reinterpret_cast<const uint16_t *>(p.g) + row;     // is the upper half of an fp32
+        const __amdgpu_buffer_rsrc_t rg =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(gb), 0, static_cast<int>(bytes / 2), 0x00020000);
+        const u2 w = __builtin_amdgcn_raw_buffer_load_b64(rg, static_cast<int>(off / 2), 0, kAuxNonTemporal);
+        g = f4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
+               __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u)};
     } else {
         const f4 h = load_quad(make_rsrc(p.h + row, bytes), off);
         const f4 c = load_quad(make_rsrc(p.c + row, bytes), off);
@@ -148,15 +156,17 @@ void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipE
 {
     const dim3 grid = (TAIL != 0 && p.worker_fastest) ? dim3(p.n_chunks * p.W) : dim3(p.n_chunks, p.W), block(kStepThreads);
     const bool has_v = p.momentum != 0.0f;
-    const int grad = p.g ? kGradExternal : (p.sigma != 0.0f ? kGradQuadNoisy : kGradQuadExact);
+    const int grad = p.g ? (p.g_bf16 ? kGradExternalBf16 : kGradExternal) : (p.sigma != 0.0f ? kGradQuadNoisy : kGradQuadExact);
     // start/stop (may be null) receive the kernel's own begin and end timestamps
 #define COCOD_LAUNCH_STEP(V, G) hipExtLaunchKernelGGL((quad_step_kernel<V, G, TAIL>), grid, block, 0, stream, start, stop, 0, p)
     if (has_v) {
         if (grad == kGradExternal)       COCOD_LAUNCH_STEP(true, kGradExternal);
+        else if (grad == kGradExternalBf16) COCOD_LAUNCH_STEP(true, kGradExternalBf16);
         else if (grad == kGradQuadNoisy) COCOD_LAUNCH_STEP(true, kGradQuadNoisy);
         else                             COCOD_LAUNCH_STEP(true, kGradQuadExact);
     } else {
         if (grad == kGradExternal)       COCOD_LAUNCH_STEP(false, kGradExternal);
+        else if (grad == kGradExternalBf16) COCOD_LAUNCH_STEP(false, kGradExternalBf16);
         else if (grad == kGradQuadNoisy) COCOD_LAUNCH_STEP(false, kGradQuadNoisy);
         else                             COCOD_LAUNCH_STEP(false, kGradQuadExact);
     }

@@ -237,6 +237,15 @@ def test_external_step_state_machine():
             assert e.value.status == P.ERR_INVALID
         ctx.external_step(g)                             # outside a round: plain SGD step
         assert ctx.get_step() == 3
-    with dry() as ctx:                                   # also legal on a context with a built-in gradient
+        ctx.external_step_bf16(g + 8)                    # 16-bit gradients need 8-byte alignment only
+        assert ctx.get_step() == 4
+        for bad in (None, g + 4):
+            with pytest.raises(P.CocodError) as e:
+                ctx.external_step_bf16(bad)
+            assert e.value.status == P.ERR_INVALID
+        ctx.average_begin()
+        ctx.external_step_bf16(g, close_round=True)
+        assert not ctx.is_averaging() and ctx.get_step() == 5
+    with dry() as ctx:                                  # also legal on a context with a built-in gradient
         ctx.external_step(g)
         assert ctx.get_step() == 1

@@ -284,3 +284,37 @@ def test_external_gradient_steps(packed, mu):
         check_state(g, o, what="external round %d" % r)
     assert g.ctx.get_step() == o.step
     g.close()
+
+
+@pytest.mark.parametrize("packed,mu", [(False, 0.9), (True, 0.9), (True, 0.0)])
+def test_external_bf16_gradient_steps(packed, mu):
+    """16-bit gradients: a noisy quadratic gradient rounded to brain floats on the host goes to the
+    oracle (widened exactly to fp64) and to the device (16-bit buffer); both apply the same update."""
+    W, k, rounds = 4, 3, 3
+    sizes = [5, 1024, 2051, 2, 1023, 4100] if packed else None
+    d = sum(sizes) if packed else 6007
+    hyper = dict(lr=0.05, momentum=mu, weight_decay=5e-4, seed=23)
+    h, c = synth_inputs.quadratic_data(29, W, d)
+    src = orc.QuadraticOracle(h, c, noise_sigma=0.01, **hyper)           # only supplies gradients
+    o = orc.QuadraticOracle(h, c, noise_sigma=0.0, **hyper)
+    g = GpuWorkers(W, d, tensor_numel=sizes, grad=P.GRAD_EXTERNAL, **hyper)
+    for r in range(rounds):
+        g.ctx.average_begin(); o.average_begin()
+        for s in range(k):
+            src.x[...] = o.x                                             # gradient at the tracked model
+            G = src.local_steps(1, log_gradients=True)[0]
+            G16 = torch.from_numpy(G.astype(np.float32)).to(torch.bfloat16)
+            assert not torch.equal(G16.float(), torch.from_numpy(G.astype(np.float32)))   # rounding really happens
+            g.ctx.sync()
+            gbuf = g._upload(G16.float().numpy()).to(torch.bfloat16)     # exact: values are 16-bit already
+            assert gbuf.is_contiguous() and gbuf.shape == (W, g.stride)
+            torch.cuda.synchronize()
+            last = s == k - 1 and r != 1
+            g.ctx.external_step_bf16(gbuf, close_round=last)
+            o.external_step(G16.double().numpy())
+        if r == 1:
+            g.ctx.average_end_apply()
+        o.average_end_apply()
+        check_state(g, o, what="bf16 external round %d" % r)
+    assert g.ctx.get_step() == o.step
+    g.close()

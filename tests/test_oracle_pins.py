@@ -298,3 +298,26 @@ def test_consensus_distance():
     # Local-SGD style averaging (a round with zero local steps) brings every worker to the mean
     big.average_begin(); big.average_end_apply()
     assert big.consensus_distance() < 1e-28
+
+
+def test_external_step_hand_values_and_replay_of_logged_gradients():
+    """The step with a given gradient: one hand-computed update (values exact in binary), and a
+    replay of another oracle's logged gradients, which must retrace that oracle bit for bit."""
+    one = np.ones((1, 1), np.float32)
+    o = orc.QuadraticOracle(one, one, x0=1.0, lr=0.125, momentum=0.5, weight_decay=0.5)
+    o.v[...] = 4.0
+    o.external_step(np.array([[2.0]]))              # g = 2 + 0.5*1 = 2.5; v = 0.5*4 + 2.5 = 4.5; x = 1 - 0.125*4.5
+    assert o.v[0, 0] == 4.5 and o.x[0, 0] == 0.4375 and o.step == 1
+    W, d, k = 3, 257, 4
+    h, c = synth_inputs.quadratic_data(5, W, d)
+    for mu in (0.0, 0.9):
+        hyper = dict(lr=0.05, momentum=mu, weight_decay=5e-4, seed=3)
+        a = orc.QuadraticOracle(h, c, noise_sigma=0.01, **hyper)
+        b = orc.QuadraticOracle(h, c, noise_sigma=0.0, **hyper)
+        for r in range(3):
+            a.average_begin(); b.average_begin()
+            for G in a.local_steps(k, log_gradients=True):
+                b.external_step(G)
+            a.average_end_apply(); b.average_end_apply()
+        assert np.array_equal(a.x, b.x) and a.step == b.step
+        assert mu == 0.0 or np.array_equal(a.v, b.v)
