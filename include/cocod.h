@@ -196,6 +196,23 @@ int cocod_external_step(cocod_ctx *ctx, const float *g, int close_round);
  */
 int cocod_external_step_bf16(cocod_ctx *ctx, const uint16_t *g, int close_round);
 
+/*
+ * One whole pass of the while-loop body of Algorithm 1 (Step I and Step II side by side, then line
+ * 6 and line 7) replayed from a HIP graph: the same kernels, in the same order and on the same two
+ * branches, as cocod_average_begin + cocod_local_steps(k) + cocod_average_end_apply (fused_tail == 0)
+ * or cocod_average_begin + cocod_local_steps_end_apply(k) (fused_tail != 0), with bit-identical
+ * results, but submitted with ONE call instead of one per kernel and event: for small models, where
+ * the launches and not the memory traffic bound a round.  The first call for a given (k, fused_tail,
+ * schedule, live buffer) records and instantiates the graph (this allocates, and is the only slow
+ * call); later calls only launch it on compute_stream.  The averaging branch runs inside the graph,
+ * not on avg_stream.  Kernels in the graph read the step counter t from a device word the library
+ * owns, so a replay continues the noise stream exactly where eager calls would.  Graph rounds and
+ * the eager calls may be mixed freely between rounds.  cocod_set_lr drops the recorded graphs (it
+ * then waits for compute_stream).  Launches inside a graph are not seen by cocod_step_timing.
+ * Only legal while IDLE (COCOD_ERR_STATE otherwise); k >= 0; needs a built-in gradient when k > 0.
+ */
+int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail);
+
 /* Choose how Step I is scheduled; only legal while IDLE.  Default COCOD_SCHED_OVERLAP. */
 int cocod_set_schedule(cocod_ctx *ctx, int schedule);
 

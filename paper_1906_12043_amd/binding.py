@@ -65,6 +65,7 @@ def lib():
             "cocod_local_steps_end_apply": ([vp, i32], i32),
             "cocod_external_step": ([vp, vp, i32], i32),
             "cocod_external_step_bf16": ([vp, vp, i32], i32),
+            "cocod_graph_round": ([vp, i32, i32], i32),
             "cocod_average_begin": ([vp], i32),
             "cocod_average_end_apply": ([vp], i32),
             "cocod_set_schedule": ([vp, i32], i32),
@@ -218,6 +219,10 @@ class Context:
         """One round with line 6 applied inside the last local step."""
         self.average_begin()
         self.local_steps_end_apply(k)
+
+    def graph_round(self, k, fused_tail=True):
+        """One round replayed from a HIP graph (recorded on first use)."""
+        return _check(lib().cocod_graph_round(self.handle, k, int(fused_tail)), self.handle)
 
     def round(self, k):
         """One pass of the while-loop body of Algorithm 1."""

@@ -40,6 +40,13 @@ struct cocod_ctx {
     std::vector<hipEvent_t> t_start, t_stop;   // event pool for step timing (owned)
     std::vector<char> t_kind;           // per timed launch: 0 plain step, 1 step with line 6
     size_t t_used = 0;
+    // replayable rounds: one instantiated graph per (k, variant, schedule, which buffer is live)
+    struct RoundGraph { int k; int fused_tail; int schedule; bool live_is_A; hipGraphExec_t exec; };
+    std::vector<RoundGraph> graphs;     // owned
+    uint32_t *d_step = nullptr;         // device copy of t that captured kernels read (owned)
+    uint64_t d_step_value = ~0ull;      // what *d_step holds once the work queued on the compute stream has run
+    bool capturing = false;             // enqueue_step runs under stream capture: step relative to *d_step
+    uint64_t capture_base = 0;          // value of `step` when the capture began
     std::string err;
 };
 
@@ -190,6 +197,8 @@ void release(cocod_ctx *ctx)
         if (ctx->d_weights) (void)hipFree(ctx->d_weights);
         if (ctx->mlp_ws) (void)hipFree(ctx->mlp_ws);
         if (ctx->d_reduce) (void)hipFree(ctx->d_reduce);
+        if (ctx->d_step) (void)hipFree(ctx->d_step);
+        for (auto &g : ctx->graphs) (void)hipGraphExecDestroy(g.exec);
         if (ctx->ev_snap) (void)hipEventDestroy(ctx->ev_snap);
         if (ctx->ev_mean) (void)hipEventDestroy(ctx->ev_mean);
         for (hipEvent_t e : ctx->t_start) (void)hipEventDestroy(e);
@@ -350,7 +359,8 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.weight_decay = ctx->cfg.weight_decay;
         p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
-        p.step = static_cast<uint32_t>(ctx->step);
+        p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
+        p.step_base = ctx->capturing ? ctx->d_step : nullptr;
         const bool timed = ctx->timing && ctx->t_used < ctx->t_start.size();
         if (timed) COCOD_HIP(ctx, hipEventRecord(ctx->t_start[ctx->t_used], ctx->s_compute));
         COCOD_HIP(ctx, cocod::launch_mlp_step(ctx->s_compute, p));
@@ -380,7 +390,8 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.sigma = ctx->cfg.noise_sigma;
         p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
-        p.step = static_cast<uint32_t>(ctx->step);
+        p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
+        p.step_base = ctx->capturing ? ctx->d_step : nullptr;
         p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes ? 1u : 0u;
         hipEvent_t t0 = nullptr, t1 = nullptr;
         if (ctx->timing && ctx->t_used < ctx->t_start.size()) {
@@ -538,6 +549,85 @@ int cocod_average_end_apply(cocod_ctx *ctx)
     return COCOD_OK;
 }
 
+// Record one round into a graph.  Nothing executes; the context's state is put back afterwards.
+static int capture_round(cocod_ctx *ctx, int k, int fused_tail, hipGraphExec_t *exec)
+{
+    float *const live = ctx->live, *const spare = ctx->spare;
+    const uint64_t step = ctx->step;
+    const bool timing = ctx->timing;
+    ctx->timing = false;
+    ctx->capturing = true;
+    ctx->capture_base = step;
+    hipError_t e = hipStreamBeginCapture(ctx->s_compute, hipStreamCaptureModeThreadLocal);
+    int rc = e == hipSuccess ? COCOD_OK : hip_fail(ctx, e, "hipStreamBeginCapture");
+    hipGraph_t graph = nullptr;
+    if (rc == COCOD_OK) {
+        rc = cocod_average_begin(ctx);
+        if (rc == COCOD_OK) {
+            if (fused_tail) {
+                rc = cocod_local_steps_end_apply(ctx, k);
+            } else {
+                rc = cocod_local_steps(ctx, k);
+                if (rc == COCOD_OK) rc = cocod_average_end_apply(ctx);
+            }
+        }
+        if (rc == COCOD_OK && k > 0) {
+            e = cocod::launch_add_word(ctx->s_compute, ctx->d_step, static_cast<uint32_t>(k));
+            if (e != hipSuccess) rc = hip_fail(ctx, e, "launch_add_word");
+        }
+        e = hipStreamEndCapture(ctx->s_compute, &graph);          // always: leaves the stream usable
+        if (rc == COCOD_OK && e != hipSuccess) rc = hip_fail(ctx, e, "hipStreamEndCapture");
+    }
+    ctx->live = live; ctx->spare = spare; ctx->snap = nullptr;
+    ctx->averaging = false; ctx->store_pending = false;
+    ctx->step = step;
+    ctx->timing = timing;
+    ctx->capturing = false;
+    if (rc == COCOD_OK) {
+        e = hipGraphInstantiate(exec, graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) rc = hip_fail(ctx, e, "hipGraphInstantiate");
+    }
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+}
+
+int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    if (ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_graph_round: a round is already open");
+    int rc = check_steps(ctx, k);
+    if (rc == COCOD_OK && k > 0) rc = need_builtin_gradient(ctx);
+    if (rc != COCOD_OK) return rc;
+    fused_tail = fused_tail != 0;
+    if (ctx->dry) {                                  // state transitions only
+        rc = cocod_average_begin(ctx);
+        if (rc == COCOD_OK) rc = fused_tail ? cocod_local_steps_end_apply(ctx, k) : cocod_local_steps(ctx, k);
+        if (rc == COCOD_OK && !fused_tail) rc = cocod_average_end_apply(ctx);
+        return rc;
+    }
+    if (!ctx->d_step) COCOD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->d_step), sizeof(uint32_t)));
+    const bool live_is_A = ctx->live == ctx->cfg.xA;
+    hipGraphExec_t exec = nullptr;
+    for (const auto &g : ctx->graphs)
+        if (g.k == k && g.fused_tail == fused_tail && g.schedule == ctx->schedule && g.live_is_A == live_is_A) exec = g.exec;
+    if (!exec) {
+        rc = capture_round(ctx, k, fused_tail, &exec);
+        if (rc != COCOD_OK) return rc;
+        ctx->graphs.push_back({k, fused_tail, ctx->schedule, live_is_A, exec});
+    }
+    if (ctx->d_step_value != ctx->step) {            // eager calls since the last replay moved t
+        COCOD_HIP(ctx, cocod::launch_set_word(ctx->s_compute, ctx->d_step, static_cast<uint32_t>(ctx->step)));
+        ctx->d_step_value = ctx->step;
+    }
+    COCOD_HIP(ctx, hipGraphLaunch(exec, ctx->s_compute));
+    if (k > 0) {                                     // what the round's calls would have done to the host state
+        float *t = ctx->live; ctx->live = ctx->spare; ctx->spare = t;
+        ctx->step += static_cast<uint64_t>(k);
+        ctx->d_step_value = ctx->step;
+    }
+    return COCOD_OK;
+}
+
 int cocod_set_schedule(cocod_ctx *ctx, int schedule)
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
@@ -545,13 +635,18 @@ int cocod_set_schedule(cocod_ctx *ctx, int schedule)
         return fail(ctx, COCOD_ERR_INVALID, "unknown schedule %d", schedule);
     if (ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_set_schedule: not while a round is open");
     ctx->schedule = schedule;
-    return COCOD_OK;
+    return COCOD_OK;                     // graphs are keyed by schedule: nothing to drop
 }
 
 int cocod_set_lr(cocod_ctx *ctx, float lr)
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
     if (!std::isfinite(lr)) return fail(ctx, COCOD_ERR_INVALID, "lr is not finite");
+    if (lr != ctx->cfg.lr && !ctx->graphs.empty()) {     // captured kernels carry the old step size
+        COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+        for (auto &g : ctx->graphs) (void)hipGraphExecDestroy(g.exec);
+        ctx->graphs.clear();
+    }
     ctx->cfg.lr = lr;
     return COCOD_OK;
 }

@@ -54,7 +54,22 @@ __global__ __launch_bounds__(kFillThreads) void copy_kernel(const float *src, fl
     __builtin_nontemporal_store(t, reinterpret_cast<f4 *>(dst) + q);
 }
 
+__global__ void set_word_kernel(uint32_t *word, uint32_t value) { *word = value; }
+__global__ void add_word_kernel(uint32_t *word, uint32_t inc) { *word += inc; }
+
 }  // namespace
+
+hipError_t launch_set_word(hipStream_t stream, uint32_t *word, uint32_t value)
+{
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(1), 0, stream, word, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_word(hipStream_t stream, uint32_t *word, uint32_t inc)
+{
+    hipLaunchKernelGGL(add_word_kernel, dim3(1), dim3(1), 0, stream, word, inc);
+    return hipGetLastError();
+}
 
 hipError_t launch_copy(hipStream_t stream, const float *src, float *dst, uint64_t n_quads)
 {

@@ -36,7 +36,8 @@ struct StepParams {
     const float *mean;   //           x = mean + (x_new - snap); mean is [stride], valid when snap is set
     float lr, momentum, weight_decay, sigma;
     uint32_t key0, key1; // generator key (seed low, seed high)
-    uint32_t step;       // global step counter t
+    uint32_t step;       // global step counter t (relative to *step_base when that is set)
+    const uint32_t *step_base;   // non-null inside a replayable graph: device word holding t at the start of the replay
     uint32_t worker_fastest;   // line-6 step only: order blocks worker-fastest (mean larger than the cache)
 };
 
@@ -75,6 +76,7 @@ struct MlpParams {
     float *v;                 // momentum, unused when momentum == 0
     float lr, momentum, weight_decay;
     uint32_t key0, key1, step;
+    const uint32_t *step_base;   // as in StepParams
     // work space owned by the context
     float *X;                 // [W][batch][n_in]
     float *H;                 // [W][batch][n_hid]  relu output
@@ -88,6 +90,10 @@ size_t mlp_dz_pitch();
 hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p);
 
 hipError_t launch_copy(hipStream_t stream, const float *src, float *dst, uint64_t n_quads);
+
+// *word = value  /  *word += inc : the device copy of the step counter that graph replays read
+hipError_t launch_set_word(hipStream_t stream, uint32_t *word, uint32_t value);
+hipError_t launch_add_word(hipStream_t stream, uint32_t *word, uint32_t inc);
 
 hipError_t launch_debug_normals(hipStream_t stream, uint32_t key0, uint32_t key1, uint32_t tag,
                                 uint32_t worker, uint32_t step, uint64_t j0, uint64_t n, int fast,

@@ -67,15 +67,16 @@ __device__ __forceinline__ void sgd_update(const MlpParams &p, uint64_t at, floa
 __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
 {
     const uint32_t worker = blockIdx.y;
+    const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;
     const uint64_t n_quads = static_cast<uint64_t>(p.batch) * p.n_in / 4;
     const uint64_t q = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (q < n_quads) {
-        const Normals4 z = box_muller_fast(philox4x32_10(static_cast<uint32_t>(q), p.step, worker, kTagMlpX, p.key0, p.key1));
+        const Normals4 z = box_muller_fast(philox4x32_10(static_cast<uint32_t>(q), step, worker, kTagMlpX, p.key0, p.key1));
         float *X = p.X + static_cast<uint64_t>(worker) * p.batch * p.n_in;
         *reinterpret_cast<f4 *>(X + q * 4) = f4{z.z[0], z.z[1], z.z[2], z.z[3]};
     }
     if (blockIdx.x == 0 && threadIdx.x < p.batch / 4) {
-        const Words4 r = philox4x32_10(threadIdx.x, p.step, worker, kTagMlpY, p.key0, p.key1);
+        const Words4 r = philox4x32_10(threadIdx.x, step, worker, kTagMlpY, p.key0, p.key1);
         #pragma unroll
         for (int i = 0; i < 4; ++i)
             p.y[static_cast<uint64_t>(worker) * p.batch + threadIdx.x * 4 + i] =

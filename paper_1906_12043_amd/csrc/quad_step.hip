@@ -58,8 +58,10 @@ __device__ __forceinline__ void store_quad(__amdgpu_buffer_rsrc_t r, uint32_t by
 // Must be called by all threads of the block (it synchronises when shift != 0).
 __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const StepParams &p, uint32_t worker)
 {
+    const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;      // wave-uniform
+
     const Normals4 a = box_muller_fast(
-        philox4x32_10(static_cast<uint32_t>(q), p.step, worker, kTagNoise, p.key0, p.key1));
+        philox4x32_10(static_cast<uint32_t>(q), step, worker, kTagNoise, p.key0, p.key1));
     if (shift == 0) return f4{a.z[0], a.z[1], a.z[2], a.z[3]};          // block-uniform branch
     __shared__ float first_of_wave[kStepThreads / 64][3];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -71,7 +73,7 @@ __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const S
             b0 = first_of_wave[wave + 1][0]; b1 = first_of_wave[wave + 1][1]; b2 = first_of_wave[wave + 1][2];
         } else {                                                        // one lane of one wave per block
             const Normals4 nb = box_muller_fast(
-                philox4x32_10(static_cast<uint32_t>(q + 1), p.step, worker, kTagNoise, p.key0, p.key1));
+                philox4x32_10(static_cast<uint32_t>(q + 1), step, worker, kTagNoise, p.key0, p.key1));
             b0 = nb.z[0]; b1 = nb.z[1]; b2 = nb.z[2];
         }
     }
@@ -157,8 +159,15 @@ void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipE
     const dim3 grid = (TAIL != 0 && p.worker_fastest) ? dim3(p.n_chunks * p.W) : dim3(p.n_chunks, p.W), block(kStepThreads);
     const bool has_v = p.momentum != 0.0f;
     const int grad = p.g ? (p.g_bf16 ? kGradExternalBf16 : kGradExternal) : (p.sigma != 0.0f ? kGradQuadNoisy : kGradQuadExact);
-    // start/stop (may be null) receive the kernel's own begin and end timestamps
-#define COCOD_LAUNCH_STEP(V, G) hipExtLaunchKernelGGL((quad_step_kernel<V, G, TAIL>), grid, block, 0, stream, start, stop, 0, p)
+    // start/stop receive the kernel's own begin and end timestamps; without them an ordinary launch
+    // (the only kind a stream capture records)
+#define COCOD_LAUNCH_STEP(V, G)                                                                                   \
+    do {                                                                                                          \
+        if (start || stop)                                                                                        \
+            hipExtLaunchKernelGGL((quad_step_kernel<V, G, TAIL>), grid, block, 0, stream, start, stop, 0, p);     \
+        else                                                                                                      \
+            hipLaunchKernelGGL((quad_step_kernel<V, G, TAIL>), grid, block, 0, stream, p);                        \
+    } while (0)
     if (has_v) {
         if (grad == kGradExternal)       COCOD_LAUNCH_STEP(true, kGradExternal);
         else if (grad == kGradExternalBf16) COCOD_LAUNCH_STEP(true, kGradExternalBf16);

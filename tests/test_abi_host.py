@@ -249,3 +249,27 @@ def test_external_step_state_machine():
     with dry() as ctx:                                  # also legal on a context with a built-in gradient
         ctx.external_step(g)
         assert ctx.get_step() == 1
+
+
+def test_graph_round_state_machine():
+    with dry() as ctx:
+        a = ctx.live_model()
+        ctx.graph_round(3, fused_tail=True)
+        assert ctx.get_step() == 3 and not ctx.is_averaging() and ctx.live_model() != a
+        ctx.graph_round(2, fused_tail=False)
+        assert ctx.get_step() == 5 and ctx.live_model() == a
+        ctx.graph_round(0)                                   # pure averaging: no buffer swap, no step
+        assert ctx.get_step() == 5 and ctx.live_model() == a
+        ctx.average_begin()
+        with pytest.raises(P.CocodError) as e:
+            ctx.graph_round(1)
+        assert e.value.status == P.ERR_STATE
+        ctx.average_end_apply()
+        with pytest.raises(P.CocodError) as e:
+            ctx.graph_round(-1)
+        assert e.value.status == P.ERR_INVALID
+    with dry(grad=P.GRAD_EXTERNAL, h=None, c=None) as ctx:
+        with pytest.raises(P.CocodError) as e:
+            ctx.graph_round(1)
+        assert e.value.status == P.ERR_INVALID
+        ctx.graph_round(0)

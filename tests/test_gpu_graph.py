@@ -1,0 +1,97 @@
+"""A round replayed from a HIP graph (cocod_graph_round) must give the bits of the same round issued
+call by call, on every replay, with eager work and synchronisations between replays, and must follow
+the oracle like any other round of Algorithm 1."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1906_12043_amd as P
+import synth_inputs
+from oracle import cocod_oracle as orc
+from oracle import mlp_oracle
+from gpu_harness import GpuWorkers, rel_err
+from test_gpu_mlp import GpuMlp
+
+pytestmark = pytest.mark.gpu
+
+HYPER = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=91)
+
+
+def eager_round(ctx, k, fused_tail):
+    if fused_tail:
+        ctx.round_fused_tail(k)
+    else:
+        ctx.round(k)
+
+
+def same_bits(a, b, what):
+    a.ctx.sync(); b.ctx.sync()
+    assert a.ctx.get_step() == b.ctx.get_step(), what
+    assert (a.ctx.live_model() == a.xA.data_ptr()) == (b.ctx.live_model() == b.xA.data_ptr()), what
+    real = (lambda t: t[..., :a.d]) if a.pos is None else (lambda t: t[..., a.pos])   # pads hold unspecified values
+    assert torch.equal(real(a.live()), real(b.live())), what + ": x"
+    assert torch.equal(real(a.v), real(b.v)), what + ": v"
+    assert torch.equal(real(a.mean), real(b.mean)), what + ": mean"
+
+
+@pytest.mark.parametrize("packed,two_streams,fused_tail,schedule", [
+    (False, True, True, P.SCHED_OVERLAP),
+    (True, True, False, P.SCHED_OVERLAP),
+    (False, False, True, P.SCHED_OVERLAP),
+    (True, True, True, P.SCHED_SERIAL),
+    (False, True, False, P.SCHED_FUSED),
+])
+def test_graph_rounds_match_eager_rounds_bit_for_bit(packed, two_streams, fused_tail, schedule):
+    W, k, rounds = 5, 2, 9
+    sizes = [3, 2048, 1025, 6, 5000] if packed else None
+    d = sum(sizes) if packed else 20011
+    h, c = synth_inputs.quadratic_data(8, W, d)
+    make = lambda: GpuWorkers(W, d, h=h, c=c, two_streams=two_streams, tensor_numel=sizes, **HYPER)
+    e, g = make(), make()
+    for w in (e, g):
+        w.ctx.set_schedule(schedule)
+    o = orc.QuadraticOracle(h, c, **HYPER)
+    for r in range(rounds):
+        eager_round(e.ctx, k, fused_tail)
+        if r in (2, 5):                              # eager rounds between replays: both graphs (one per
+            eager_round(g.ctx, k, fused_tail)        # live buffer) are replayed before and after them
+        else:
+            g.ctx.graph_round(k, fused_tail)
+        o.round(k)
+        same_bits(e, g, "round %d" % r)
+    assert rel_err(g.x(), o.x) <= 1e-5 and rel_err(g.vel(), o.v) <= 1e-4
+    # eager local steps outside a round move t; the next replay must pick the new value up
+    e.ctx.local_steps(3); g.ctx.local_steps(3)
+    eager_round(e.ctx, k, fused_tail); g.ctx.graph_round(k, fused_tail)
+    same_bits(e, g, "after eager local steps")
+    # a new step size drops the recorded graphs; a set step counter is honoured
+    for w in (e, g):
+        w.ctx.set_lr(0.02)
+        w.ctx.set_step(1000)
+    for r in range(3):
+        eager_round(e.ctx, k, fused_tail); g.ctx.graph_round(k, fused_tail)
+        same_bits(e, g, "after set_lr, round %d" % r)
+    # other periods share the context: k = 0 (pure averaging), k = 1 (the step reads the stored models), k = 3
+    for kk in (0, 1, 3, 1, 0, 3):
+        eager_round(e.ctx, kk, fused_tail); g.ctx.graph_round(kk, fused_tail)
+        same_bits(e, g, "k=%d" % kk)
+    e.close(); g.close()
+
+
+def test_graph_rounds_of_mlp_workers_match_eager_rounds_and_oracle():
+    W, shape, batch, k, rounds = 3, (128, 64, 10), 128, 2, 5
+    theta0 = synth_inputs.mlp_he_init(11, *shape)
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=1e-3, seed=0x5EED0004)
+    e, g = GpuMlp(W, shape, batch, theta0, **hyper), GpuMlp(W, shape, batch, theta0, **hyper)
+    o = mlp_oracle.MlpOracle(theta0, W, *shape, batch, **hyper)
+    for r in range(rounds):
+        e.ctx.round(k)
+        if r == 2:
+            g.ctx.round(k)
+        else:
+            g.ctx.graph_round(k, fused_tail=False)
+        o.round(k)
+        assert np.array_equal(e.x(), g.x()) and np.array_equal(e.vel(), g.vel()), r
+        assert e.ctx.get_step() == g.ctx.get_step() == o.step
+    assert rel_err(g.x(), o.x) <= 1e-4 and rel_err(g.vel(), o.v) <= 1e-4
+    e.close(); g.close()
