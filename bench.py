@@ -46,7 +46,7 @@ def tail_step_bytes(W, d, k):
 
 
 def moved_round_bytes(W, d, k, variant):
-    if variant == "separate":
+    if variant in ("separate", "graph_separate"):
         return model_round_bytes(W, d, k)
     return W * d * (STEP_BYTES * (k - 1) + 4 * (1 + 1 / W)) + tail_step_bytes(W, d, k)
 
@@ -56,6 +56,9 @@ def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
     kernels' own start/stop timestamps on the compute stream, the average duration in seconds of the
     plain step kernel and of the step kernel that carries line 6 (None where there was no launch)."""
     def one_round():
+        if variant.startswith("graph"):          # the whole round as one graph launch
+            ctx.graph_round(k, variant == "graph_fused_tail")
+            return
         ctx.average_begin()
         if variant == "separate":
             ctx.local_steps(k)
@@ -65,6 +68,7 @@ def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
     for _ in range(warmup):
         one_round()
     ctx.sync()
+    want_step_times = want_step_times and not variant.startswith("graph")   # launches in a graph are not timed
     ctx.step_timing(rounds * k if want_step_times else 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -168,6 +172,7 @@ def bench_mlp(args):
                     lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"],
                     compute_stream=s_compute, avg_stream=s_avg)
     per_round, step_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "separate")
+    graph_round, _, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "graph_separate")
     n_in, n_hid, n_out = shape
     gemm_flops = W * 2 * (2 * batch * n_in * n_hid)
     all_flops = gemm_flops + W * 3 * (2 * batch * n_hid * n_out)
@@ -180,6 +185,7 @@ def bench_mlp(args):
         "config": {"workload": "C4 MLP workers 3072-1024-10, batch 128 fresh N(0,1) inputs per worker-step, momentum 0.9, "
                                "lr 0.05", "k": k, "W": W, "d": d, "variant": "separate"},
         "local_step_ms": step_s * 1e3,
+        "graph_ms_per_round": graph_round * 1e3,
         "local_step_TFLOPs_all": all_flops / step_s / 1e12,
         "roofline": {"bound": "mfma", "kernel": "one local step (6 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
                      "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -290,7 +296,7 @@ def main():
             out["roofline_line6_step"] = tail
     if not args.headline_only:
         variants = {}
-        for name in ("separate", "fused_tail"):
+        for name in ("separate", "fused_tail", "graph_separate", "graph_fused_tail"):
             sweep = {}
             for kk in cfg["k"]:
                 pr, ps, ts = time_rounds(ctx, torch, kk, args.steps, 2, name)
