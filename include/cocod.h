@@ -98,6 +98,10 @@ typedef struct cocod_config {
     float noise_sigma;             /* sigma of the gradient noise (quadratic kind) */
     uint64_t seed;                 /* key of the counter-based generator */
     const float *weights;          /* host, [W], p_i = M_i / sum M_l, must sum to 1 within 1e-4; NULL = 1/W */
+    const float *noise_sigma_w;    /* host, [W], copied; NULL = noise_sigma for every worker.  Heterogeneous
+                                      workers (quadratic kind): worker i's mini-batch of M_i samples has
+                                      gradient variance sigma^2 / M_i (bounded-variance assumption), so the
+                                      caller passes sigma / sqrt(M_i); each finite and >= 0 */
     float *xA;                     /* device [W][stride]: holds the models at create time (the live buffer) */
     float *xB;                     /* device [W][stride]: second model buffer; need not be initialised */
     float *v;                      /* device [W][stride]: momentum buffer, caller-initialised (0 for a fresh

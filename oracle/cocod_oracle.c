@@ -173,12 +173,15 @@ void oracle_fill_quadratic(uint64_t seed, int W, size_t n, const uint64_t *idx, 
  */
 void oracle_local_step(int W, size_t n, const uint64_t *idx, REAL *x, REAL *v,
                        const float *h, const float *c, double lr, double mu, double wd,
-                       double sigma, uint64_t seed, uint32_t step, REAL *g_out)
+                       double sigma_all, const float *sigma_w, uint64_t seed, uint32_t step, REAL *g_out)
 {
     #pragma omp parallel for schedule(static)
     for (int i = 0; i < W; ++i) {
         uint64_t cached_q = UINT64_MAX;
         double z[4] = { 0, 0, 0, 0 };
+        /* heterogeneous workers: the variance of worker i's mini-batch gradient falls with its
+           batch size M_i, so each worker may carry its own standard deviation */
+        const double sigma = sigma_w ? (double)sigma_w[i] : sigma_all;
         for (size_t m = 0; m < n; ++m) {
             size_t at = (size_t)i * n + m;
             uint64_t j = column_index(idx, m);
@@ -245,12 +248,12 @@ void oracle_correct(int W, size_t n, REAL *x, const REAL *snap, const REAL *mean
  */
 void oracle_round(int W, size_t n, const uint64_t *idx, REAL *x, REAL *v, REAL *snap, REAL *mean,
                   const float *h, const float *c, const double *p, double lr, double mu,
-                  double wd, double sigma, uint64_t seed, uint32_t step0, int k)
+                  double wd, double sigma, const float *sigma_w, uint64_t seed, uint32_t step0, int k)
 {
     for (size_t at = 0; at < (size_t)W * n; ++at) snap[at] = x[at];
     oracle_mean(W, n, snap, p, mean);
     for (int s = 0; s < k; ++s)
-        oracle_local_step(W, n, idx, x, v, h, c, lr, mu, wd, sigma, seed, step0 + (uint32_t)s, NULL);
+        oracle_local_step(W, n, idx, x, v, h, c, lr, mu, wd, sigma, sigma_w, seed, step0 + (uint32_t)s, NULL);
     oracle_correct(W, n, x, snap, mean);
 }
 

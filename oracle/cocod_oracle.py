@@ -30,11 +30,11 @@ def _lib(kind):
         lib.oracle_uniforms.argtypes = [u64, u32, u32, u32, u64, u64, ptr]
         lib.oracle_raw_words.argtypes = [u64, u32, u32, u32, u64, u64, ptr]
         lib.oracle_fill_quadratic.argtypes = [u64, i32, sz, ptr, ptr, ptr]
-        lib.oracle_local_step.argtypes = [i32, sz, ptr, ptr, ptr, ptr, ptr, dbl, dbl, dbl, dbl, u64, u32, ptr]
+        lib.oracle_local_step.argtypes = [i32, sz, ptr, ptr, ptr, ptr, ptr, dbl, dbl, dbl, dbl, ptr, u64, u32, ptr]
         lib.oracle_mean.argtypes = [i32, sz, ptr, ptr, ptr]
         lib.oracle_correct.argtypes = [i32, sz, ptr, ptr, ptr]
         lib.oracle_round.argtypes = [i32, sz, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr,
-                                     dbl, dbl, dbl, dbl, u64, u32, i32]
+                                     dbl, dbl, dbl, dbl, ptr, u64, u32, i32]
         for name in ("oracle_philox4x32_10", "oracle_words", "oracle_normal_quad", "oracle_normals",
                      "oracle_uniforms", "oracle_raw_words", "oracle_fill_quadratic", "oracle_local_step",
                      "oracle_mean", "oracle_correct", "oracle_round"):
@@ -105,7 +105,7 @@ class QuadraticOracle:
     """
 
     def __init__(self, h, c, x0=None, *, lr, momentum=0.0, weight_decay=0.0, noise_sigma=0.0,
-                 seed=0, idx=None, weights=None, kind="f64"):
+                 seed=0, idx=None, weights=None, noise_sigma_w=None, kind="f64"):
         self.lib = _lib(kind)
         self.real = np.float64 if kind == "f64" else np.float32
         assert self.lib.oracle_real_bytes() == np.dtype(self.real).itemsize
@@ -124,6 +124,8 @@ class QuadraticOracle:
         self.seed = int(seed)
         self.idx = None if idx is None else np.ascontiguousarray(idx, dtype=np.uint64)
         self.p = None if weights is None else np.ascontiguousarray(weights, dtype=np.float64)
+        self.sigma_w = None if noise_sigma_w is None else np.ascontiguousarray(noise_sigma_w, dtype=np.float32)
+        assert self.sigma_w is None or self.sigma_w.shape == (self.W,)
         self.step = 0
         self.averaging = False
 
@@ -133,7 +135,7 @@ class QuadraticOracle:
         for _ in range(k):
             g = np.zeros_like(self.x) if log_gradients else None
             self.lib.oracle_local_step(self.W, self.n, _p(self.idx), _p(self.x), _p(self.v), _p(self.h),
-                                       _p(self.c), self.lr, self.momentum, self.wd, self.sigma,
+                                       _p(self.c), self.lr, self.momentum, self.wd, self.sigma, _p(self.sigma_w),
                                        self.seed, self.step, _p(g))
             self.step += 1
             if log_gradients:
@@ -174,5 +176,5 @@ class QuadraticOracle:
         """One pass of the while-loop body through the single C routine."""
         self.lib.oracle_round(self.W, self.n, _p(self.idx), _p(self.x), _p(self.v), _p(self.snap),
                               _p(self.mean), _p(self.h), _p(self.c), _p(self.p), self.lr, self.momentum,
-                              self.wd, self.sigma, self.seed, self.step, k)
+                              self.wd, self.sigma, _p(self.sigma_w), self.seed, self.step, k)
         self.step += k

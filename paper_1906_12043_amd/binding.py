@@ -22,7 +22,7 @@ class Config(C.Structure):
         ("n_tensors", C.c_uint32), ("grad", C.c_uint32),
         ("tensor_numel", C.POINTER(C.c_uint64)), ("bucket_bytes", C.c_uint64),
         ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float), ("noise_sigma", C.c_float),
-        ("seed", C.c_uint64), ("weights", C.POINTER(C.c_float)),
+        ("seed", C.c_uint64), ("weights", C.POINTER(C.c_float)), ("noise_sigma_w", C.POINTER(C.c_float)),
         ("xA", C.c_void_p), ("xB", C.c_void_p), ("v", C.c_void_p), ("mean", C.c_void_p),
         ("h", C.c_void_p), ("c", C.c_void_p), ("stride", C.c_uint64),
         ("compute_stream", C.c_void_p), ("avg_stream", C.c_void_p),
@@ -130,7 +130,7 @@ def debug_copy(stream, src, dst, n):
 # ---- the five entry points of the round, by their C names -----------------------------------
 
 def cocod_create(*, W, d, xA, xB, mean, stride, v=None, h=None, c=None, lr, momentum=0.0, weight_decay=0.0,
-                 noise_sigma=0.0, seed=0, tensor_numel=None, bucket_bytes=0, weights=None,
+                 noise_sigma=0.0, seed=0, tensor_numel=None, bucket_bytes=0, weights=None, noise_sigma_w=None,
                  compute_stream=None, avg_stream=None, grad=GRAD_QUADRATIC, mlp=(0, 0, 0, 0), flags=0):
     """Returns an opaque context handle (int)."""
     cfg = Config()
@@ -148,6 +148,10 @@ def cocod_create(*, W, d, xA, xB, mean, stride, v=None, h=None, c=None, lr, mome
         warr = (C.c_float * len(weights))(*weights)
         keep.append(warr)
         cfg.weights = warr
+    if noise_sigma_w is not None:
+        sarr = (C.c_float * len(noise_sigma_w))(*noise_sigma_w)
+        keep.append(sarr)
+        cfg.noise_sigma_w = sarr
     cfg.xA, cfg.xB, cfg.v, cfg.mean = _addr(xA), _addr(xB), _addr(v), _addr(mean)
     cfg.h, cfg.c, cfg.stride = _addr(h), _addr(c), stride
     cfg.compute_stream, cfg.avg_stream = _addr(compute_stream), _addr(avg_stream)

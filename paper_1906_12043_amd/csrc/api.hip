@@ -22,6 +22,7 @@ struct cocod_ctx {
     std::vector<Chunk> chunks;
     Chunk *d_chunks = nullptr;          // device copy of the chunk table (owned)
     float *d_weights = nullptr;         // device copy of p_i (owned), nullptr = uniform
+    float *d_sigma_w = nullptr;         // device copy of the per-worker noise scale (owned), nullptr = cfg.noise_sigma
     double *d_reduce = nullptr;         // scratch of the consensus-distance reduction (owned, allocated on first use)
     float *mlp_ws = nullptr;            // MLP kind: work space (owned); mlp holds the pointers carved from it
     cocod::MlpParams mlp{};
@@ -175,6 +176,10 @@ int validate(const cocod_config *cfg, uint64_t padded_d)
         }
         if (std::fabs(sum - 1.0) > 1e-4) return fail(nullptr, COCOD_ERR_INVALID, "weights sum to %g, not 1", sum);
     }
+    if (cfg->noise_sigma_w)
+        for (uint32_t i = 0; i < cfg->W; ++i)
+            if (!(cfg->noise_sigma_w[i] >= 0.0f) || !std::isfinite(cfg->noise_sigma_w[i]))
+                return fail(nullptr, COCOD_ERR_INVALID, "noise_sigma_w[%u] must be finite and >= 0", i);
     if (cfg->grad == COCOD_GRAD_MLP) {
         const uint64_t want = static_cast<uint64_t>(cfg->mlp_in) * cfg->mlp_hidden + cfg->mlp_hidden +
                               static_cast<uint64_t>(cfg->mlp_hidden) * cfg->mlp_out + cfg->mlp_out;
@@ -195,6 +200,7 @@ void release(cocod_ctx *ctx)
     if (!ctx->dry) {
         if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
         if (ctx->d_weights) (void)hipFree(ctx->d_weights);
+        if (ctx->d_sigma_w) (void)hipFree(ctx->d_sigma_w);
         if (ctx->mlp_ws) (void)hipFree(ctx->mlp_ws);
         if (ctx->d_reduce) (void)hipFree(ctx->d_reduce);
         if (ctx->d_step) (void)hipFree(ctx->d_step);
@@ -282,6 +288,9 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
     std::vector<float> weights;
     if (cfg->weights) weights.assign(cfg->weights, cfg->weights + cfg->W);
     ctx->cfg.weights = nullptr;
+    std::vector<float> sigma_w;
+    if (cfg->noise_sigma_w && cfg->grad == COCOD_GRAD_QUADRATIC) sigma_w.assign(cfg->noise_sigma_w, cfg->noise_sigma_w + cfg->W);
+    ctx->cfg.noise_sigma_w = nullptr;
 
     if (!ctx->dry) {
         hipError_t e = hipMalloc(reinterpret_cast<void **>(&ctx->d_chunks), ctx->chunks.size() * sizeof(Chunk));
@@ -291,6 +300,11 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
             e = hipMalloc(reinterpret_cast<void **>(&ctx->d_weights), weights.size() * sizeof(float));
             if (e == hipSuccess)
                 e = hipMemcpy(ctx->d_weights, weights.data(), weights.size() * sizeof(float), hipMemcpyHostToDevice);
+        }
+        if (e == hipSuccess && !sigma_w.empty()) {
+            e = hipMalloc(reinterpret_cast<void **>(&ctx->d_sigma_w), sigma_w.size() * sizeof(float));
+            if (e == hipSuccess)
+                e = hipMemcpy(ctx->d_sigma_w, sigma_w.data(), sigma_w.size() * sizeof(float), hipMemcpyHostToDevice);
         }
         if (e == hipSuccess && cfg->grad == COCOD_GRAD_MLP) {      // one work-space block, carved below
             const size_t wb = static_cast<size_t>(cfg->W) * cfg->mlp_batch;
@@ -388,6 +402,7 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.momentum = ctx->cfg.momentum;
         p.weight_decay = ctx->cfg.weight_decay;
         p.sigma = ctx->cfg.noise_sigma;
+        p.sigma_w = ctx->d_sigma_w;
         p.key0 = static_cast<uint32_t>(ctx->cfg.seed);
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);

@@ -35,6 +35,7 @@ struct StepParams {
     const float *snap;   // non-null: this is the last step of a round and line 6 is applied to its result
     const float *mean;   //           x = mean + (x_new - snap); mean is [stride], valid when snap is set
     float lr, momentum, weight_decay, sigma;
+    const float *sigma_w; // non-null: device [W], worker i's noise standard deviation instead of sigma
     uint32_t key0, key1; // generator key (seed low, seed high)
     uint32_t step;       // global step counter t (relative to *step_base when that is set)
     const uint32_t *step_base;   // non-null inside a replayable graph: device word holding t at the start of the replay

@@ -136,7 +136,7 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     }
 
     if (GRAD == kGradQuadNoisy)
-        g += p.sigma * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, shift, p, worker);
+        g += (p.sigma_w ? p.sigma_w[worker] : p.sigma) * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, shift, p, worker);
     g += p.weight_decay * x0;
     f4 v = v0;
     if (HAS_V) { v = p.momentum * v0 + g; g = v; }
@@ -158,7 +158,7 @@ void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipE
 {
     const dim3 grid = (TAIL != 0 && p.worker_fastest) ? dim3(p.n_chunks * p.W) : dim3(p.n_chunks, p.W), block(kStepThreads);
     const bool has_v = p.momentum != 0.0f;
-    const int grad = p.g ? (p.g_bf16 ? kGradExternalBf16 : kGradExternal) : (p.sigma != 0.0f ? kGradQuadNoisy : kGradQuadExact);
+    const int grad = p.g ? (p.g_bf16 ? kGradExternalBf16 : kGradExternal) : (p.sigma != 0.0f || p.sigma_w ? kGradQuadNoisy : kGradQuadExact);
     // start/stop receive the kernel's own begin and end timestamps; without them an ordinary launch
     // (the only kind a stream capture records)
 #define COCOD_LAUNCH_STEP(V, G)                                                                                   \

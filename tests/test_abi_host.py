@@ -113,6 +113,7 @@ def dry(**over):
     (dict(lr=float("nan")), "lr"), (dict(momentum=1.0), "momentum"), (dict(momentum=-0.1), "momentum"),
     (dict(weight_decay=-1.0), "weight_decay"), (dict(noise_sigma=-1.0), "noise_sigma"),
     (dict(weights=[0.5, 0.5, 0.5, 0.5]), "weights sum"), (dict(weights=[1.5, -0.5, 0, 0]), "weights["),
+    (dict(noise_sigma_w=[0.1, -0.1, 0, 0]), "noise_sigma_w[1]"), (dict(noise_sigma_w=[0, 0, 0, float("inf")]), "noise_sigma_w[3]"),
     (dict(tensor_numel=[500, 400]), "sum to"), (dict(grad=7), "gradient kind"), (dict(flags=1 | 64), "flag"),
 ])
 def test_create_rejects_bad_arguments(over, needle):

@@ -133,6 +133,29 @@ def test_weighted_mean():
     g.close()
 
 
+def test_heterogeneous_workers_weighted_mean_and_per_worker_noise():
+    """Workers with mini-batch sizes M_i: mean weights M_i / sum M and noise sigma / sqrt(M_i)."""
+    W, k = 5, 3
+    sizes = [1030, 7, 4099, 2]
+    d = sum(sizes)
+    M = np.array([32, 64, 64, 128, 256], dtype=np.float64)
+    p = (M / M.sum()).tolist()
+    sigma_w = (0.08 / np.sqrt(M)).astype(np.float32).tolist()
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=123.0, seed=31)   # noise_sigma is overridden
+    h, c = synth_inputs.quadratic_data(3, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, weights=p, noise_sigma_w=sigma_w, **hyper)
+    o = orc.QuadraticOracle(h, c, weights=p, noise_sigma_w=sigma_w, **hyper)
+    for r in range(4):
+        if r % 2:
+            g.ctx.round_fused_tail(k)
+        else:
+            g.ctx.round(k)
+        o.round(k)
+        check_state(g, o, what="round %d" % r)
+    assert abs(g.ctx.consensus_distance() - o.consensus_distance()) <= 1e-5 * o.consensus_distance()
+    g.close()
+
+
 # ---- schedules and layouts give the same bits ----------------------------------------------------
 
 def run_bits(W, d, rounds, k, schedule, two_streams, tensor_numel=None, bucket_bytes=0):

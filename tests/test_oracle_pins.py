@@ -300,6 +300,29 @@ def test_consensus_distance():
     assert big.consensus_distance() < 1e-28
 
 
+def test_per_worker_noise_scale():
+    """sigma_i per worker: (a) equal entries are the scalar sigma; (b) with zero curvature, step size 1
+    and a start at 0 the first step lands on -sigma_i z_i, the generator's own normals; (c) a worker
+    with sigma_i = 0 follows the noiseless trajectory whatever the others do."""
+    W, d = 3, 515
+    h, c = synth_inputs.quadratic_data(9, W, d)
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, seed=77)
+    a = orc.QuadraticOracle(h, c, noise_sigma=0.02, **hyper)
+    b = orc.QuadraticOracle(h, c, noise_sigma=9.0, noise_sigma_w=[0.02] * W, **hyper)
+    a.round(3); b.round(3)
+    assert np.array_equal(a.x, b.x) and np.array_equal(a.v, b.v)
+    sig = np.array([0.5, 0.0, 2.0], dtype=np.float32)
+    z = orc.QuadraticOracle(np.zeros((W, d)), np.zeros((W, d)), lr=1.0, seed=77, noise_sigma_w=sig)
+    z.local_steps(1)
+    for i in range(W):
+        assert np.array_equal(z.x[i], -float(sig[i]) * orc.normals(77, orc.TAG_NOISE, i, 0, 0, d))
+    assert np.all(z.x[1] == 0) and np.std(z.x[2]) > 3 * np.std(z.x[0]) > 0
+    quiet = orc.QuadraticOracle(h, c, noise_sigma=0.0, **hyper)
+    mixed = orc.QuadraticOracle(h, c, noise_sigma_w=[0.1, 0.0, 0.3], **hyper)
+    quiet.local_steps(4); mixed.local_steps(4)
+    assert np.array_equal(quiet.x[1], mixed.x[1]) and not np.array_equal(quiet.x[0], mixed.x[0])
+
+
 def test_external_step_hand_values_and_replay_of_logged_gradients():
     """The step with a given gradient: one hand-computed update (values exact in binary), and a
     replay of another oracle's logged gradients, which must retrace that oracle bit for bit."""
