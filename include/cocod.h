@@ -257,6 +257,15 @@ int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches
  */
 int cocod_consensus_distance(cocod_ctx *ctx, double *result);
 
+/*
+ * Diagnostic (quadratic kind only): the objective of the paper's problem definition,
+ * f(x) = sum_i p_i f_i(x) with f_i(x) = 1/2 sum_j h_ij (x_j - c_ij)^2, evaluated at the averaged
+ * model x^ = sum_i p_i x^i of the live models, and || grad f(x^) ||^2, the quantity whose running
+ * mean Theorem 1 bounds.  Real parameters only.  Same scheduling, waiting and scratch behaviour as
+ * cocod_consensus_distance; both results are host doubles.  COCOD_ERR_INVALID for other kinds.
+ */
+int cocod_quadratic_objective(cocod_ctx *ctx, double *f_at_mean, double *grad_norm_sq_at_mean);
+
 /* Block the host until both streams have drained. */
 int cocod_sync(cocod_ctx *ctx);
 

@@ -172,6 +172,20 @@ class QuadraticOracle:
         xbar = p @ x
         return float(np.sum(p[:, None] * (x - xbar[None, :]) ** 2))
 
+    def objective(self, x):
+        """f(x) = sum_i p_i f_i(x), f_i(x) = 1/2 sum_j h_ij (x_j - c_ij)^2: the problem definition's
+        objective for the quadratic workers, at one point x [n].  Returns (f, grad f [n])."""
+        p = np.full(self.W, 1.0 / self.W) if self.p is None else self.p
+        diff = np.asarray(x, dtype=np.float64)[None, :] - self.c.astype(np.float64)
+        hd = self.h.astype(np.float64) * diff
+        return float(0.5 * np.sum(p[:, None] * hd * diff)), p @ hd
+
+    def objective_at_mean(self):
+        """(f(xbar), ||grad f(xbar)||^2) at xbar = sum_i p_i x_i, the point Theorem 1 speaks about."""
+        p = np.full(self.W, 1.0 / self.W) if self.p is None else self.p
+        f, grad = self.objective(p @ self.x.astype(np.float64))
+        return f, float(grad @ grad)
+
     def round(self, k):
         """One pass of the while-loop body through the single C routine."""
         self.lib.oracle_round(self.W, self.n, _p(self.idx), _p(self.x), _p(self.v), _p(self.snap),

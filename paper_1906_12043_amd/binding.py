@@ -76,6 +76,7 @@ def lib():
             "cocod_is_averaging": ([vp], i32),
             "cocod_get_plan": ([vp, P(u64), P(u32), P(u32)], i32),
             "cocod_consensus_distance": ([vp, P(C.c_double)], i32),
+            "cocod_quadratic_objective": ([vp, P(C.c_double), P(C.c_double)], i32),
             "cocod_fill_quadratic": ([vp], i32),
             "cocod_mlp_workspace": ([vp, P(vp), P(vp), P(vp), P(vp), P(vp), P(u32)], i32),
             "cocod_step_timing": ([vp, i32], i32),
@@ -277,6 +278,12 @@ class Context:
         out = C.c_double()
         _check(lib().cocod_consensus_distance(self.handle, C.byref(out)), self.handle)
         return out.value
+
+    def quadratic_objective(self):
+        """(f(x^), ||grad f(x^)||^2) at the weighted mean of the live models."""
+        f, g = C.c_double(), C.c_double()
+        _check(lib().cocod_quadratic_objective(self.handle, C.byref(f), C.byref(g)), self.handle)
+        return f.value, g.value
 
     def mlp_workspace(self):
         """Device addresses {X, H, dA, dZ, y} of the MLP work space and the row pitch of dZ."""

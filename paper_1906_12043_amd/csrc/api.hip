@@ -745,12 +745,33 @@ int cocod_consensus_distance(cocod_ctx *ctx, double *result)
     *result = 0.0;
     if (ctx->dry) return COCOD_OK;
     const uint32_t n_chunks = static_cast<uint32_t>(ctx->chunks.size());
-    if (!ctx->d_reduce)
-        COCOD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->d_reduce), (static_cast<size_t>(n_chunks) + 1) * sizeof(double)));
+    if (!ctx->d_reduce)     // two results, then two runs of block partials
+        COCOD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->d_reduce), (static_cast<size_t>(n_chunks) + 1) * 2 * sizeof(double)));
     COCOD_HIP(ctx, cocod::launch_consensus_distance(ctx->s_compute, ctx->d_chunks, n_chunks, ctx->live, ctx->cfg.stride,
-                                                    ctx->cfg.W, ctx->d_weights, ctx->d_reduce + 1, ctx->d_reduce));
+                                                    ctx->cfg.W, ctx->d_weights, ctx->d_reduce + 2, ctx->d_reduce));
     COCOD_HIP(ctx, hipMemcpyAsync(result, ctx->d_reduce, sizeof(double), hipMemcpyDeviceToHost, ctx->s_compute));
     COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    return COCOD_OK;
+}
+
+int cocod_quadratic_objective(cocod_ctx *ctx, double *f_at_mean, double *grad_norm_sq_at_mean)
+{
+    if (!ctx || !f_at_mean || !grad_norm_sq_at_mean)
+        return fail(nullptr, COCOD_ERR_INVALID, "ctx, f_at_mean and grad_norm_sq_at_mean must not be NULL");
+    *f_at_mean = *grad_norm_sq_at_mean = 0.0;
+    if (ctx->cfg.grad != COCOD_GRAD_QUADRATIC) return fail(ctx, COCOD_ERR_INVALID, "not a quadratic-gradient context");
+    if (ctx->dry) return COCOD_OK;
+    const uint32_t n_chunks = static_cast<uint32_t>(ctx->chunks.size());
+    if (!ctx->d_reduce)
+        COCOD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->d_reduce), (static_cast<size_t>(n_chunks) + 1) * 2 * sizeof(double)));
+    COCOD_HIP(ctx, cocod::launch_quadratic_objective(ctx->s_compute, ctx->d_chunks, n_chunks, ctx->live, ctx->cfg.h, ctx->cfg.c,
+                                                     ctx->cfg.stride, ctx->cfg.W, ctx->d_weights, ctx->d_reduce + 2,
+                                                     ctx->d_reduce));
+    double both[2] = {0.0, 0.0};
+    COCOD_HIP(ctx, hipMemcpyAsync(both, ctx->d_reduce, sizeof both, hipMemcpyDeviceToHost, ctx->s_compute));
+    COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    *f_at_mean = both[0];
+    *grad_norm_sq_at_mean = both[1];
     return COCOD_OK;
 }
 

@@ -211,15 +211,68 @@ __global__ __launch_bounds__(kStepThreads) void consensus_partial_kernel(const C
     }
 }
 
+// block b adds the b-th run of n block partials into out[b]
 __global__ __launch_bounds__(256) void consensus_final_kernel(const double *partial, uint32_t n, double *out)
 {
     __shared__ double wave_part[4];
+    partial += static_cast<uint64_t>(blockIdx.x) * n;
     double local = 0.0;
     for (uint32_t i = threadIdx.x; i < n; i += 256) local += partial[i];
     local = wave_sum_f64(local);
     if (threadIdx.x % 64 == 0) wave_part[threadIdx.x / 64] = local;
     __syncthreads();
-    if (threadIdx.x == 0) out[0] = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
+    if (threadIdx.x == 0) out[blockIdx.x] = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
+}
+
+// ---- the objective of the paper's problem definition at the averaged model ------------------------
+// f(xbar) = sum_i p_i f_i(xbar) with the workers' quadratics f_i(x) = 1/2 sum_j h_ij (x_j - c_ij)^2 and
+// xbar = sum_i p_i x_i, and || grad f(xbar) ||^2 (the quantity whose running mean Theorem 1 bounds),
+// grad f(xbar)_j = sum_i p_i h_ij (xbar_j - c_ij).  Same reduction structure as the consensus distance;
+// partial holds two runs of gridDim.x doubles (objective, squared gradient norm).
+template <bool WEIGHTED>
+__global__ __launch_bounds__(kStepThreads) void objective_partial_kernel(const Chunk *table, const float *x, const float *h,
+                                                                         const float *c, uint64_t stride, uint32_t W,
+                                                                         const float *weights, double *partial)
+{
+    __shared__ double wave_part[2][kStepThreads / 64];
+    const Chunk ck = table[blockIdx.x];
+    const uint32_t e = threadIdx.x * 4;
+    double f_local = 0.0, g_local = 0.0;
+    if (e < ck.n) {
+        const uint64_t at = static_cast<uint64_t>(ck.mem_quad) * 4 + e;
+        const float uniform = 1.0f / static_cast<float>(W);
+        float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t i = 0; i < W; ++i) {
+            const float4 r = ld4(x + at + static_cast<uint64_t>(i) * stride);
+            const float pw = WEIGHTED ? weights[i] : uniform;
+            m.x += pw * r.x; m.y += pw * r.y; m.z += pw * r.z; m.w += pw * r.w;
+        }
+        float4 f = make_float4(0.f, 0.f, 0.f, 0.f), g = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t i = 0; i < W; ++i) {
+            const float4 hr = ld4(h + at + static_cast<uint64_t>(i) * stride);
+            const float4 cr = ld4(c + at + static_cast<uint64_t>(i) * stride);
+            const float pw = WEIGHTED ? weights[i] : uniform;
+            const float4 dl = make_float4(m.x - cr.x, m.y - cr.y, m.z - cr.z, m.w - cr.w);
+            g.x += pw * hr.x * dl.x; g.y += pw * hr.y * dl.y; g.z += pw * hr.z * dl.z; g.w += pw * hr.w * dl.w;
+            f.x += pw * hr.x * dl.x * dl.x; f.y += pw * hr.y * dl.y * dl.y;
+            f.z += pw * hr.z * dl.z * dl.z; f.w += pw * hr.w * dl.w * dl.w;
+        }
+        const uint32_t keep = ck.n - e;                   // alignment pads of a tensor's tail quad do not count
+        f_local = static_cast<double>(f.x);              g_local = static_cast<double>(g.x) * g.x;
+        if (keep > 1) { f_local += static_cast<double>(f.y); g_local += static_cast<double>(g.y) * g.y; }
+        if (keep > 2) { f_local += static_cast<double>(f.z); g_local += static_cast<double>(g.z) * g.z; }
+        if (keep > 3) { f_local += static_cast<double>(f.w); g_local += static_cast<double>(g.w) * g.w; }
+        f_local *= 0.5;
+    }
+    f_local = wave_sum_f64(f_local);
+    g_local = wave_sum_f64(g_local);
+    if (threadIdx.x % 64 == 0) { wave_part[0][threadIdx.x / 64] = f_local; wave_part[1][threadIdx.x / 64] = g_local; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        double s = 0.0;
+        for (uint32_t w = 0; w < kStepThreads / 64; ++w) s += wave_part[threadIdx.x][w];
+        partial[static_cast<uint64_t>(threadIdx.x) * gridDim.x + blockIdx.x] = s;
+    }
 }
 
 inline uint32_t blocks_for(uint64_t n_quads) { return static_cast<uint32_t>((n_quads + kAvgThreads - 1) / kAvgThreads); }
@@ -274,6 +327,16 @@ hipError_t launch_consensus_distance(hipStream_t stream, const Chunk *table, uin
     if (weights) hipLaunchKernelGGL((consensus_partial_kernel<true>), dim3(n_chunks), dim3(kStepThreads), 0, stream, table, x, stride, W, weights, partial);
     else         hipLaunchKernelGGL((consensus_partial_kernel<false>), dim3(n_chunks), dim3(kStepThreads), 0, stream, table, x, stride, W, weights, partial);
     hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, stream, partial, n_chunks, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_quadratic_objective(hipStream_t stream, const Chunk *table, uint32_t n_chunks, const float *x,
+                                      const float *h, const float *c, uint64_t stride, uint32_t W, const float *weights,
+                                      double *partial, double *out)
+{
+    if (weights) hipLaunchKernelGGL((objective_partial_kernel<true>), dim3(n_chunks), dim3(kStepThreads), 0, stream, table, x, h, c, stride, W, weights, partial);
+    else         hipLaunchKernelGGL((objective_partial_kernel<false>), dim3(n_chunks), dim3(kStepThreads), 0, stream, table, x, h, c, stride, W, weights, partial);
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(2), dim3(256), 0, stream, partial, n_chunks, out);
     return hipGetLastError();
 }
 

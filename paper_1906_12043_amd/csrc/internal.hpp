@@ -64,6 +64,12 @@ hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, 
 hipError_t launch_consensus_distance(hipStream_t stream, const Chunk *table, uint32_t n_chunks, const float *x,
                                      uint64_t stride, uint32_t W, const float *weights, double *partial, double *out);
 
+// out[0] = f(xbar) = sum_i p_i 1/2 sum_j h_ij (xbar_j - c_ij)^2, out[1] = || grad f(xbar) ||^2, xbar = sum_i p_i x_i;
+// partial: 2 * n_chunks doubles of scratch
+hipError_t launch_quadratic_objective(hipStream_t stream, const Chunk *table, uint32_t n_chunks, const float *x,
+                                      const float *h, const float *c, uint64_t stride, uint32_t W, const float *weights,
+                                      double *partial, double *out);
+
 hipError_t launch_fill_quadratic(hipStream_t stream, const Chunk *table, uint32_t n_chunks, uint32_t W,
                                  uint64_t stride, uint64_t padded_d, float *h, float *c,
                                  uint32_t key0, uint32_t key1);

@@ -55,7 +55,7 @@ class GpuWorkers:
     def _upload(self, arr):
         buf = torch.zeros((self.W, self.stride), device=self.dev)
         if arr is not None:
-            src = torch.from_numpy(np.ascontiguousarray(np.broadcast_to(arr, (self.W, self.d)), dtype=np.float32)).to(self.dev)
+            src = torch.from_numpy(np.array(np.broadcast_to(arr, (self.W, self.d)), dtype=np.float32)).to(self.dev)
             if self.pos is None:
                 buf[:, :self.d] = src
             else:

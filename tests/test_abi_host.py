@@ -274,3 +274,12 @@ def test_graph_round_state_machine():
             ctx.graph_round(1)
         assert e.value.status == P.ERR_INVALID
         ctx.graph_round(0)
+
+
+def test_diagnostics_on_dry_contexts():
+    with dry() as ctx:
+        assert ctx.consensus_distance() == 0.0 and ctx.quadratic_objective() == (0.0, 0.0)
+    with dry(grad=P.GRAD_EXTERNAL, h=None, c=None) as ctx:
+        with pytest.raises(P.CocodError) as e:
+            ctx.quadratic_objective()
+        assert e.value.status == P.ERR_INVALID

@@ -258,11 +258,18 @@ def test_consensus_distance_and_local_sgd_schedule(packed, weights):
     g = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
     o = orc.QuadraticOracle(h, c, **hyper)
     assert g.ctx.consensus_distance() == 0.0
+    f0, g0 = g.ctx.quadratic_objective()                                 # at x = 0
+    want_f0, want_g0 = o.objective_at_mean()
+    assert abs(f0 - want_f0) <= 1e-5 * want_f0 and abs(g0 - want_g0) <= 1e-5 * want_g0
     for r in range(3):
         g.ctx.round(k); o.round(k)
         got, want = g.ctx.consensus_distance(), o.consensus_distance()
         assert want > 0 and abs(got - want) <= 1e-5 * want, (got, want)
         assert g.ctx.consensus_distance() == got                         # deterministic reduction
+        (f, g2), (want_f, want_g2) = g.ctx.quadratic_objective(), o.objective_at_mean()
+        assert abs(f - want_f) <= 1e-5 * want_f and abs(g2 - want_g2) <= 1e-5 * want_g2, (f, want_f, g2, want_g2)
+        assert g.ctx.quadratic_objective() == (f, g2) and g.ctx.consensus_distance() == got
+        assert f < f0 and g2 < g0                                        # the workers are descending
     for schedule in (P.SCHED_OVERLAP, P.SCHED_FUSED):                    # Local-SGD rounds
         g.ctx.set_schedule(schedule)
         g.ctx.local_steps(k); g.ctx.average_begin(); g.ctx.average_end_apply()

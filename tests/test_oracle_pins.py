@@ -300,6 +300,46 @@ def test_consensus_distance():
     assert big.consensus_distance() < 1e-28
 
 
+def test_objective_and_gradient_norm():
+    """f = sum_i p_i f_i and its gradient: hand values, the minimiser's closed form, and the analytic
+    gradient against central differences of f itself."""
+    # one worker, unit curvature: f = 1/2 ||x - c||^2, ||grad f||^2 = 2 f
+    c1 = np.array([[1.0, -2.0, 0.5]], np.float32)
+    o = orc.QuadraticOracle(np.ones((1, 3), np.float32), c1, x0=[2.0, 0.0, 0.5], lr=0.1)
+    f, g2 = o.objective_at_mean()
+    assert f == 0.5 * (1.0 + 4.0) and g2 == 5.0
+    # two weighted workers, one coordinate: f(x) = 0.25*1/2*2*(x-1)^2 + 0.75*1/2*4*(x+1)^2
+    h = np.array([[2.0], [4.0]], np.float32); c = np.array([[1.0], [-1.0]], np.float32)
+    o = orc.QuadraticOracle(h, c, lr=0.1, weights=[0.25, 0.75])
+    o.x[...] = [[3.0], [1.0]]                                 # xbar = 0.75 + 0.75 = 1.5
+    f, g2 = o.objective_at_mean()
+    assert abs(f - (0.25 * 0.25 + 1.5 * 6.25)) < 1e-15       # 0.25*(0.5)^2 + 1.5*(2.5)^2
+    assert abs(g2 - (0.25 * 2 * 0.5 + 0.75 * 4 * 2.5) ** 2) < 1e-12
+    # minimiser x*_j = sum_i p_i h_ij c_ij / sum_i p_i h_ij: gradient vanishes there, f is larger nearby
+    W, d = 4, 9
+    h, c = synth_inputs.quadratic_data(21, W, d)
+    p = np.array([0.1, 0.2, 0.3, 0.4])
+    o = orc.QuadraticOracle(h, c, lr=0.1, weights=p)
+    hp = p[:, None] * h.astype(np.float64)
+    xstar = np.sum(hp * c, axis=0) / np.sum(hp, axis=0)
+    fstar, grad = o.objective(xstar)
+    assert np.max(np.abs(grad)) < 1e-14
+    rng = np.random.default_rng(0)
+    for _ in range(5):
+        assert o.objective(xstar + 0.1 * rng.standard_normal(d))[0] > fstar
+    # analytic gradient vs central differences (f is quadratic: central differences are exact up to rounding)
+    x = rng.standard_normal(d)
+    _, grad = o.objective(x)
+    for j in range(d):
+        e = np.zeros(d); e[j] = 1e-3
+        num = (o.objective(x + e)[0] - o.objective(x - e)[0]) / 2e-3
+        assert abs(num - grad[j]) < 1e-9
+    # all workers at the same point: objective_at_mean is objective(that point)
+    o.x[...] = x
+    f, g2 = o.objective_at_mean()
+    assert abs(f - o.objective(x)[0]) < 1e-14 and abs(g2 - grad @ grad) < 1e-12
+
+
 def test_per_worker_noise_scale():
     """sigma_i per worker: (a) equal entries are the scalar sigma; (b) with zero curvature, step size 1
     and a start at 0 the first step lands on -sigma_i z_i, the generator's own normals; (c) a worker
