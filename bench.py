@@ -46,15 +46,28 @@ def tail_step_bytes(W, d, k):
 
 
 def moved_round_bytes(W, d, k, variant):
+    if variant.startswith("head_"):              # no pass for the mean: only its store, and its read by line 6
+        sub = moved_round_bytes(W, d, k, variant[len("head_"):])
+        rides = k >= 2 or (k == 1 and variant.endswith("separate"))    # else the mean is a pass of its own
+        return sub - W * d * 4 if rides else sub
     if variant in ("separate", "graph_separate"):
         return model_round_bytes(W, d, k)
     return W * d * (STEP_BYTES * (k - 1) + 4 * (1 + 1 / W)) + tail_step_bytes(W, d, k)
+
+
+LAST_HEAD_STEP_S = [None]     # average duration of the mean-forming first step in the last time_rounds call
 
 
 def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
     """Seconds per round over `rounds` timed rounds and, measured over the same rounds from the
     kernels' own start/stop timestamps on the compute stream, the average duration in seconds of the
     plain step kernel and of the step kernel that carries line 6 (None where there was no launch)."""
+    import paper_1906_12043_amd as P
+    head = variant.startswith("head_")           # Step I inside the round's first step (one stream)
+    if head:
+        variant = variant[len("head_"):]
+        ctx.set_schedule(P.SCHED_HEAD)
+
     def one_round():
         if variant.startswith("graph"):          # the whole round as one graph launch
             ctx.graph_round(k, variant == "graph_fused_tail")
@@ -77,12 +90,15 @@ def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
     ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    avg = [None, None]
+    avg = [None, None, None]
     if want_step_times:
         for i, (total_ms, n) in enumerate(ctx.step_timing_read()):
             if n:
                 avg[i] = total_ms / n / 1e3
         ctx.step_timing(0)
+    LAST_HEAD_STEP_S[0] = avg[2]
+    if head:
+        ctx.set_schedule(P.SCHED_OVERLAP)
     return elapsed / rounds, avg[0], avg[1]
 
 
@@ -296,7 +312,8 @@ def main():
             out["roofline_line6_step"] = tail
     if not args.headline_only:
         variants = {}
-        for name in ("separate", "fused_tail", "graph_separate", "graph_fused_tail"):
+        for name in ("separate", "fused_tail", "graph_separate", "graph_fused_tail", "head_separate", "head_fused_tail",
+                     "head_graph_fused_tail"):
             sweep = {}
             for kk in cfg["k"]:
                 pr, ps, ts = time_rounds(ctx, torch, kk, args.steps, 2, name)
@@ -304,7 +321,8 @@ def main():
                                       "model_GBps": model_round_bytes(W, d, kk) / pr / 1e9,
                                       "moved_GBps": moved_round_bytes(W, d, kk, name) / pr / 1e9,
                                       "plain_step_ms": ps * 1e3 if ps else None,
-                                      "tail_step_ms": ts * 1e3 if ts else None}
+                                      "tail_step_ms": ts * 1e3 if ts else None,
+                                      "head_step_ms": LAST_HEAD_STEP_S[0] * 1e3 if LAST_HEAD_STEP_S[0] else None}
             variants[name] = sweep
         out["k_sweep"] = variants
         sched = {}

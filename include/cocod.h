@@ -59,12 +59,17 @@ typedef enum cocod_grad_kind {
     COCOD_GRAD_EXTERNAL = 2
 } cocod_grad_kind;
 
-/* How Step I is scheduled relative to Step II (the arithmetic is the same in all three). */
+/* How Step I is scheduled relative to Step II (the arithmetic is the same in all of them). */
 typedef enum cocod_schedule {
     COCOD_SCHED_OVERLAP = 0,   /* mean on avg_stream, concurrent with the local steps (the paper's scheme) */
     COCOD_SCHED_SERIAL = 1,    /* mean on compute_stream after the local steps, then line 6 (sequential, as
                                   the paper's Local-SGD timeline) */
-    COCOD_SCHED_FUSED = 2      /* mean and line 6 in one kernel after the local steps */
+    COCOD_SCHED_FUSED = 2,     /* mean and line 6 in one kernel after the local steps */
+    COCOD_SCHED_HEAD = 3       /* mean formed inside the first local step of the round, which reads every
+                                  stored model anyway: Step I costs one 4/W-byte store per parameter and no
+                                  pass of its own (built-in quadratic gradient; whenever the round's first
+                                  step is not such a step, the mean is formed on compute_stream just before
+                                  line 6 needs it) */
 } cocod_schedule;
 
 enum {
@@ -243,10 +248,11 @@ int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks,
  * context); n = 0 switches it off.  cocod_step_timing_read waits for compute_stream, returns the
  * summed kernel durations and the number of launches measured since the last read, and rearms.
  * Index 0 of both arrays: plain local steps; index 1: steps that carry line 6
- * (cocod_local_steps_end_apply's last step).
+ * (cocod_local_steps_end_apply's last step); index 2: first steps of a round that also form the
+ * mean (COCOD_SCHED_HEAD).
  */
 int cocod_step_timing(cocod_ctx *ctx, int max_launches);
-int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches[2]);
+int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[3], uint32_t launches[3]);
 
 /*
  * Diagnostic: the weighted consensus distance sum_i p_i || x^ - x^i ||^2 of the live models, with

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 OK, ERR_INVALID, ERR_STATE, ERR_HIP, ERR_NOMEM, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 GRAD_QUADRATIC, GRAD_MLP, GRAD_EXTERNAL = 0, 1, 2
-SCHED_OVERLAP, SCHED_SERIAL, SCHED_FUSED = 0, 1, 2
+SCHED_OVERLAP, SCHED_SERIAL, SCHED_FUSED, SCHED_HEAD = 0, 1, 2, 3
 FLAG_DRY_RUN = 1
 
 
@@ -269,10 +269,11 @@ class Context:
         return _check(lib().cocod_step_timing(self.handle, max_launches), self.handle)
 
     def step_timing_read(self):
-        """[(summed kernel milliseconds, launches)] for plain steps and for steps carrying line 6."""
-        total, n = (C.c_double * 2)(), (C.c_uint32 * 2)()
+        """[(summed kernel milliseconds, launches)] for plain steps, for steps carrying line 6 and for
+        first steps of a round that also form the mean."""
+        total, n = (C.c_double * 3)(), (C.c_uint32 * 3)()
         _check(lib().cocod_step_timing_read(self.handle, total, n), self.handle)
-        return [(total[0], n[0]), (total[1], n[1])]
+        return [(total[i], n[i]) for i in range(3)]
 
     def consensus_distance(self):
         out = C.c_double()

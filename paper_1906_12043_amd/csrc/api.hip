@@ -34,6 +34,7 @@ struct cocod_ctx {
     const float *snap = nullptr;        // stored models x_t^i of the open round (aliases one of the two)
     bool averaging = false;             // a round is open
     bool store_pending = false;         // next local step must write out of place (keeps the stored models intact)
+    bool mean_pending = false;          // the open round's mean has not been enqueued yet (every schedule but OVERLAP)
     int schedule = COCOD_SCHED_OVERLAP;
     uint64_t step = 0;                  // global step counter t
     bool dry = false;
@@ -219,6 +220,20 @@ int enqueue_mean(cocod_ctx *ctx, hipStream_t stream)
     for (size_t b = 0; b + 1 < ctx->bucket_begin.size(); ++b)
         COCOD_HIP(ctx, cocod::launch_wmean(stream, ctx->snap, ctx->cfg.stride, ctx->cfg.W, ctx->bucket_begin[b],
                                            ctx->bucket_begin[b + 1], ctx->d_weights, ctx->cfg.mean));
+    return COCOD_OK;
+}
+
+// Make the open round's mean available to line 6 on the compute stream: enqueue it there if no
+// earlier call has (sequential schedules), or join the averaging stream (overlapped schedule).
+int mean_before_line6(cocod_ctx *ctx)
+{
+    if (ctx->mean_pending) {
+        const int rc = enqueue_mean(ctx, ctx->s_compute);
+        if (rc != COCOD_OK) return rc;
+        ctx->mean_pending = false;
+    } else if (ctx->schedule == COCOD_SCHED_OVERLAP && ctx->s_avg != ctx->s_compute) {
+        COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
+    }
     return COCOD_OK;
 }
 
@@ -408,11 +423,19 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
         p.step_base = ctx->capturing ? ctx->d_step : nullptr;
         p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes ? 1u : 0u;
+        // Step I inside the round's first step: that step reads exactly the stored models
+        const bool head = ctx->schedule == COCOD_SCHED_HEAD && ctx->mean_pending && ctx->store_pending && !g_ext &&
+                          !with_line6 && ctx->cfg.grad == COCOD_GRAD_QUADRATIC;
+        if (head) {
+            p.mean_out = ctx->cfg.mean;
+            p.weights = ctx->d_weights;
+            ctx->mean_pending = false;
+        }
         hipEvent_t t0 = nullptr, t1 = nullptr;
         if (ctx->timing && ctx->t_used < ctx->t_start.size()) {
             t0 = ctx->t_start[ctx->t_used];
             t1 = ctx->t_stop[ctx->t_used];
-            ctx->t_kind[ctx->t_used] = with_line6 ? 1 : 0;
+            ctx->t_kind[ctx->t_used] = head ? 2 : (with_line6 ? 1 : 0);
             ctx->t_used += 1;
         }
         COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p, t0, t1));
@@ -450,16 +473,13 @@ static int external_step(cocod_ctx *ctx, const void *g, bool bf16, int close_rou
     int rc = check_steps(ctx, 1);
     if (rc != COCOD_OK) return rc;
     if (close_round && !ctx->dry) {      // the mean is consumed inside this step
-        if (ctx->schedule != COCOD_SCHED_OVERLAP) {
-            rc = enqueue_mean(ctx, ctx->s_compute);
-            if (rc != COCOD_OK) return rc;
-        } else if (ctx->s_avg != ctx->s_compute) {
-            COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
-        }
+        rc = mean_before_line6(ctx);
+        if (rc != COCOD_OK) return rc;
     }
     rc = enqueue_step(ctx, close_round != 0, g, bf16);
     if (rc == COCOD_OK && close_round) {
         ctx->averaging = false;
+        ctx->mean_pending = false;
         ctx->snap = nullptr;
     }
     return rc;
@@ -501,16 +521,13 @@ int cocod_local_steps_end_apply(cocod_ctx *ctx, int k)
     if (rc != COCOD_OK) return rc;
     if (!ctx->dry) {
         // the mean must be complete before the last step starts: it is consumed inside it
-        if (ctx->schedule != COCOD_SCHED_OVERLAP) {
-            rc = enqueue_mean(ctx, ctx->s_compute);
-            if (rc != COCOD_OK) return rc;
-        } else if (ctx->s_avg != ctx->s_compute) {
-            COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
-        }
+        rc = mean_before_line6(ctx);
+        if (rc != COCOD_OK) return rc;
     }
     rc = enqueue_step(ctx, true);
     if (rc != COCOD_OK) return rc;
     ctx->averaging = false;
+    ctx->mean_pending = false;
     ctx->snap = nullptr;
     return COCOD_OK;
 }
@@ -532,6 +549,7 @@ int cocod_average_begin(cocod_ctx *ctx)
     }
     ctx->averaging = true;
     ctx->store_pending = true;
+    ctx->mean_pending = ctx->schedule != COCOD_SCHED_OVERLAP;
     return COCOD_OK;
 }
 
@@ -541,18 +559,14 @@ int cocod_average_end_apply(cocod_ctx *ctx)
     if (!ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_average_end_apply: no round is open");
     if (!ctx->dry) {
         const size_t n_buckets = ctx->bucket_begin.size() - 1;
-        if (ctx->schedule == COCOD_SCHED_FUSED) {
+        if (ctx->mean_pending && ctx->schedule != COCOD_SCHED_SERIAL) {     // FUSED, or HEAD with no step to ride on
             for (size_t b = 0; b < n_buckets; ++b)
                 COCOD_HIP(ctx, cocod::launch_mean_correct(ctx->s_compute, ctx->live, ctx->snap, ctx->cfg.stride, ctx->cfg.W,
                                                           ctx->bucket_begin[b], ctx->bucket_begin[b + 1], ctx->d_weights,
                                                           ctx->cfg.mean));
         } else {
-            if (ctx->schedule == COCOD_SCHED_SERIAL) {
-                const int rc = enqueue_mean(ctx, ctx->s_compute);
-                if (rc != COCOD_OK) return rc;
-            } else if (ctx->s_avg != ctx->s_compute) {
-                COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));   // the join
-            }
+            const int rc = mean_before_line6(ctx);                                // SERIAL: the mean; OVERLAP: the join
+            if (rc != COCOD_OK) return rc;
             for (size_t b = 0; b < n_buckets; ++b)
                 COCOD_HIP(ctx, cocod::launch_correct(ctx->s_compute, ctx->live, ctx->snap, ctx->cfg.mean, ctx->cfg.stride,
                                                      ctx->cfg.W, ctx->bucket_begin[b], ctx->bucket_begin[b + 1]));
@@ -560,6 +574,7 @@ int cocod_average_end_apply(cocod_ctx *ctx)
     }
     ctx->averaging = false;
     ctx->store_pending = false;
+    ctx->mean_pending = false;
     ctx->snap = nullptr;
     return COCOD_OK;
 }
@@ -594,7 +609,7 @@ static int capture_round(cocod_ctx *ctx, int k, int fused_tail, hipGraphExec_t *
         if (rc == COCOD_OK && e != hipSuccess) rc = hip_fail(ctx, e, "hipStreamEndCapture");
     }
     ctx->live = live; ctx->spare = spare; ctx->snap = nullptr;
-    ctx->averaging = false; ctx->store_pending = false;
+    ctx->averaging = false; ctx->store_pending = false; ctx->mean_pending = false;
     ctx->step = step;
     ctx->timing = timing;
     ctx->capturing = false;
@@ -646,7 +661,8 @@ int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail)
 int cocod_set_schedule(cocod_ctx *ctx, int schedule)
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
-    if (schedule != COCOD_SCHED_OVERLAP && schedule != COCOD_SCHED_SERIAL && schedule != COCOD_SCHED_FUSED)
+    if (schedule != COCOD_SCHED_OVERLAP && schedule != COCOD_SCHED_SERIAL && schedule != COCOD_SCHED_FUSED &&
+        schedule != COCOD_SCHED_HEAD)
         return fail(ctx, COCOD_ERR_INVALID, "unknown schedule %d", schedule);
     if (ctx->averaging) return fail(ctx, COCOD_ERR_STATE, "cocod_set_schedule: not while a round is open");
     ctx->schedule = schedule;
@@ -721,17 +737,17 @@ int cocod_step_timing(cocod_ctx *ctx, int max_launches)
     return COCOD_OK;
 }
 
-int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[2], uint32_t launches[2])
+int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[3], uint32_t launches[3])
 {
     if (!ctx || !total_ms || !launches) return fail(nullptr, COCOD_ERR_INVALID, "ctx, total_ms and launches must not be NULL");
-    total_ms[0] = total_ms[1] = 0.0;
-    launches[0] = launches[1] = 0;
+    total_ms[0] = total_ms[1] = total_ms[2] = 0.0;
+    launches[0] = launches[1] = launches[2] = 0;
     if (ctx->dry) return COCOD_OK;
     COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
     for (size_t i = 0; i < ctx->t_used && i < ctx->t_stop.size(); ++i) {
         float ms = 0.0f;
         COCOD_HIP(ctx, hipEventElapsedTime(&ms, ctx->t_start[i], ctx->t_stop[i]));
-        const int kind = ctx->t_kind[i] ? 1 : 0;
+        const int kind = ctx->t_kind[i];
         total_ms[kind] += ms;
         launches[kind] += 1;
     }

@@ -55,15 +55,19 @@ __device__ __forceinline__ void store_quad(__amdgpu_buffer_rsrc_t r, uint32_t by
 // of block q and the first `shift` normals of block q + 1.  Threads own consecutive blocks, so block
 // q + 1 is the right-hand neighbour's own block: a cross-lane move inside a wave, a word of LDS
 // across a wave boundary, and one extra generator call by the block's very last thread.
-// Must be called by all threads of the block (it synchronises when shift != 0).
-__device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const StepParams &p, uint32_t worker)
+// Must be called by all threads of the block (it synchronises when shift != 0).  A kernel that calls
+// it in a loop alternates `parity` so that the LDS words of one call are not overwritten by the next
+// call while a slower wave still reads them (one barrier per call then suffices).
+__device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const StepParams &p, uint32_t worker,
+                                             uint32_t parity = 0)
 {
     const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;      // wave-uniform
 
     const Normals4 a = box_muller_fast(
         philox4x32_10(static_cast<uint32_t>(q), step, worker, kTagNoise, p.key0, p.key1));
     if (shift == 0) return f4{a.z[0], a.z[1], a.z[2], a.z[3]};          // block-uniform branch
-    __shared__ float first_of_wave[kStepThreads / 64][3];
+    __shared__ float both[2][kStepThreads / 64][3];
+    float (*first_of_wave)[3] = both[parity & 1u];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     if (lane == 0) { first_of_wave[wave][0] = a.z[0]; first_of_wave[wave][1] = a.z[1]; first_of_wave[wave][2] = a.z[2]; }
     __syncthreads();
@@ -153,6 +157,100 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     if (HAS_V) store_quad(rv, off, v);
 }
 
+// First local step of a round with Step I folded in: the step reads every worker's stored model
+// anyway, so a thread that serves one column quad for ALL W workers (as the averaging kernels do)
+// gets the weighted mean of the stored models for one extra 4/W-byte store per parameter instead of a
+// second pass over them.  The sum runs over the workers in order 0..W-1 with the same expressions as the
+// stand-alone mean kernel, so the mean has the same bits.  Loads of workers i+1 .. i+DEPTH are in flight
+// during the arithmetic of worker i.  Grid = chunks.  Walking W rows of four arrays per block streams less
+// well than the row-per-block step (measured 5.4 against 6.05 TB/s at W = 16, insensitive to prefetch depth
+// and to the row stride), which eats about half of the bytes saved.
+template <bool HAS_V, int GRAD, bool WEIGHTED, int DEPTH>
+__global__ __launch_bounds__(kStepThreads) void quad_step_head_kernel(const StepParams p)
+{
+    const Chunk ck = p.table[blockIdx.x];
+    const uint64_t col = static_cast<uint64_t>(ck.mem_quad) * 4;
+    const uint32_t bytes = ((ck.n + 3u) & ~3u) * 4u;
+    const uint32_t shift = static_cast<uint32_t>(ck.glob_off & 3u);
+    const uint32_t e = threadIdx.x * 4;
+    const uint32_t off = e * 4;
+    const uint64_t q = (ck.glob_off >> 2) + threadIdx.x;
+
+    struct Row { f4 x, v, h, c; };
+    auto load_row = [&](uint32_t w) {
+        const uint64_t row = static_cast<uint64_t>(w) * p.stride + col;
+        Row r;
+        r.x = load_quad(make_rsrc(p.x_in + row, bytes), off);
+        r.v = HAS_V ? load_quad(make_rsrc(p.v + row, bytes), off) : f4{0.f, 0.f, 0.f, 0.f};
+        r.h = load_quad(make_rsrc(p.h + row, bytes), off);
+        r.c = load_quad(make_rsrc(p.c + row, bytes), off);
+        return r;
+    };
+
+    f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+    Row ring[DEPTH];
+    #pragma unroll
+    for (int j = 0; j < DEPTH; ++j) ring[j] = load_row(static_cast<uint32_t>(j) < p.W ? j : 0);
+    for (uint32_t w0 = 0; w0 < p.W; w0 += DEPTH) {
+      #pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        const uint32_t w = w0 + j;
+        if (w >= p.W) break;
+        const Row cur = ring[j];
+        if (w + DEPTH < p.W) ring[j] = load_row(w + DEPTH);
+        const float pw = WEIGHTED ? p.weights[w] : 1.0f;
+        acc.x += pw * cur.x.x; acc.y += pw * cur.x.y; acc.z += pw * cur.x.z; acc.w += pw * cur.x.w;
+
+        f4 g = cur.h * (cur.x - cur.c);
+        if (GRAD == kGradQuadNoisy)
+            g += (p.sigma_w ? p.sigma_w[w] : p.sigma) * noise_for_quad(q, shift, p, w, w);
+        g += p.weight_decay * cur.x;
+        f4 v = cur.v;
+        if (HAS_V) { v = p.momentum * cur.v + g; g = v; }
+        f4 x = cur.x - p.lr * g;
+        if (e + 4 > ck.n && e < ck.n) {                   // tensor tail: alignment pads keep their old values
+            const uint32_t keep = ck.n - e;
+            if (keep < 2) { x.y = cur.x.y; v.y = cur.v.y; }
+            if (keep < 3) { x.z = cur.x.z; v.z = cur.v.z; }
+            x.w = cur.x.w; v.w = cur.v.w;
+        }
+        const uint64_t row = static_cast<uint64_t>(w) * p.stride + col;
+        store_quad(make_rsrc(p.x_out + row, bytes), off, x);
+        if (HAS_V) store_quad(make_rsrc(p.v + row, bytes), off, v);
+      }
+    }
+    if (!WEIGHTED) {
+        const float inv = 1.0f / static_cast<float>(p.W);
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    }
+    // the mean is read again by line 6: ordinary (cached) store
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, acc), make_rsrc(p.mean_out + col, bytes),
+                                           static_cast<int>(off), 0, 0);
+}
+
+void launch_head(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
+{
+    const dim3 grid(p.n_chunks), block(kStepThreads);
+    const bool has_v = p.momentum != 0.0f, noisy = p.sigma != 0.0f || p.sigma_w, weighted = p.weights != nullptr;
+    // rows in flight per thread: 2 measured best (1: 1 % slower, 3 and 4: more registers, no gain)
+#define COCOD_LAUNCH_HEAD_D(V, G, Wt, D)                                                                          \
+    do {                                                                                                          \
+        if (start || stop)                                                                                        \
+            hipExtLaunchKernelGGL((quad_step_head_kernel<V, G, Wt, D>), grid, block, 0, stream, start, stop, 0, p);  \
+        else                                                                                                      \
+            hipLaunchKernelGGL((quad_step_head_kernel<V, G, Wt, D>), grid, block, 0, stream, p);                     \
+    } while (0)
+#define COCOD_LAUNCH_HEAD(V, G, Wt) COCOD_LAUNCH_HEAD_D(V, G, Wt, 2)
+    if (has_v) {
+        if (noisy) { if (weighted) COCOD_LAUNCH_HEAD(true, kGradQuadNoisy, true); else COCOD_LAUNCH_HEAD(true, kGradQuadNoisy, false); }
+        else       { if (weighted) COCOD_LAUNCH_HEAD(true, kGradQuadExact, true); else COCOD_LAUNCH_HEAD(true, kGradQuadExact, false); }
+    } else {
+        if (noisy) { if (weighted) COCOD_LAUNCH_HEAD(false, kGradQuadNoisy, true); else COCOD_LAUNCH_HEAD(false, kGradQuadNoisy, false); }
+        else       { if (weighted) COCOD_LAUNCH_HEAD(false, kGradQuadExact, true); else COCOD_LAUNCH_HEAD(false, kGradQuadExact, false); }
+    }
+#undef COCOD_LAUNCH_HEAD
+}
+
 template <int TAIL>
 void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
@@ -186,7 +284,8 @@ void launch_tail(hipStream_t stream, const StepParams &p, hipEvent_t start, hipE
 
 hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
-    if (!p.snap)                 launch_tail<0>(stream, p, start, stop);
+    if (p.mean_out)              launch_head(stream, p, start, stop);     // never with line 6 or a caller's gradient
+    else if (!p.snap)            launch_tail<0>(stream, p, start, stop);
     else if (p.snap != p.x_in)   launch_tail<1>(stream, p, start, stop);
     else                         launch_tail<2>(stream, p, start, stop);
     return hipGetLastError();

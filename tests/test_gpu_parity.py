@@ -176,9 +176,39 @@ def run_bits(W, d, rounds, k, schedule, two_streams, tensor_numel=None, bucket_b
 def test_overlapped_round_is_bit_identical_to_serialised_rounds():
     W, d, rounds, k = 8, 300_001, 6, 2
     ref = run_bits(W, d, rounds, k, P.SCHED_OVERLAP, two_streams=False)
-    for schedule, two in [(P.SCHED_OVERLAP, True), (P.SCHED_SERIAL, True), (P.SCHED_FUSED, True), (P.SCHED_FUSED, False)]:
+    for schedule, two in [(P.SCHED_OVERLAP, True), (P.SCHED_SERIAL, True), (P.SCHED_FUSED, True), (P.SCHED_FUSED, False),
+                          (P.SCHED_HEAD, True), (P.SCHED_HEAD, False)]:
         got = run_bits(W, d, rounds, k, schedule, two_streams=two)
         assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]), (schedule, two)
+
+
+@pytest.mark.parametrize("weights", [None, [0.1, 0.2, 0.3, 0.15, 0.25]])
+def test_mean_formed_inside_the_first_step_gives_the_same_bits(weights):
+    """COCOD_SCHED_HEAD against the two-stream schedule: packed list with every start alignment, k = 0
+    (no step to ride on), 1 (first step is the last), 2, 3, both ways of applying line 6, mean included."""
+    W = 5
+    sizes = [5, 4096, 1, 3, 8191, 64, 4097, 2, 3000, 7]
+    d = sum(sizes)
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=78, weights=weights)
+    h, c = synth_inputs.quadratic_data(16, W, d)
+    a = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
+    b = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
+    b.ctx.set_schedule(P.SCHED_HEAD)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    for k in (2, 3, 1, 0, 2, 1):
+        for fused_tail in (False, True):
+            for w in (a, b):
+                if fused_tail:
+                    w.ctx.round_fused_tail(k)
+                else:
+                    w.ctx.round(k)
+                w.ctx.sync()
+            o.round(k)
+            for name in ("live", "v", "mean"):
+                ta, tb = (getattr(w, name)() if name == "live" else getattr(w, name) for w in (a, b))
+                assert torch.equal(ta[..., a.pos], tb[..., b.pos]), (k, fused_tail, name)
+    check_state(b, o, what="head schedule")
+    a.close(); b.close()
 
 
 def test_packed_tensor_list_is_bit_identical_to_flat_and_matches_oracle():
