@@ -75,6 +75,7 @@ def test_tiny_config_every_round():
     (1, 1, 0.0, 0.0, 0.01, 2), (1, 5, 0.9, 5e-4, 0.01, 3), (3, 3, 0.9, 0.0, 0.0, 1), (2, 4, 0.5, 0.01, 0.1, 4),
     (4, 4097, 0.9, 5e-4, 0.01, 2), (16, 10007, 0.9, 5e-4, 0.01, 2), (5, 12289, 0.0, 0.0, 0.01, 3),
     (64, 4100, 0.9, 5e-4, 0.01, 1), (7, 8192, 0.9, 0.0, 0.0, 8),
+    (1000, 5, 0.9, 5e-4, 0.01, 2), (3, 1023, 0.9, 5e-4, 0.01, 2), (3, 1025, 0.0, 5e-4, 0.01, 2), (17, 2047, 0.9, 0.0, 0.01, 3),
 ])
 def test_small_shapes_ragged_tails(W, d, mu, wd, sigma, k):
     hyper = dict(lr=0.05, momentum=mu, weight_decay=wd, noise_sigma=sigma, seed=1000 + d)
