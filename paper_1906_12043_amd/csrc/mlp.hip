@@ -86,6 +86,7 @@ __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
 
 // ---- the two big contractions ---------------------------------------------------------------------
 enum { kFwd = 0, kBwd = 1 };
+constexpr uint32_t kXcds = 8;      // accelerator complex dies of the MI355X
 
 // NWM x NWN waves per block, one 32x32 accumulator per wave: block tile (32 NWM) x (32 NWN).
 template <int EPI, int NWM, int NWN>
@@ -99,8 +100,23 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     float (*Bs)[kBK][BPITCH] = reinterpret_cast<float (*)[kBK][BPITCH]>(smem + 2 * BM * kAPitch);  // [buf][k][n]
     float (*Ct)[CPITCH] = reinterpret_cast<float (*)[CPITCH]>(smem);                               // epilogue tile
 
-    const uint32_t worker = blockIdx.z;
-    const uint32_t m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Workgroups go to the 8 XCDs (each with its own L2) round-robin by linear id.  Renumber them so
+    // that every XCD owns a CONTIGUOUS run of tiles (n fastest, then m, then worker): the tiles that
+    // share an operand panel (all n-tiles of an m-tile share its X panel, all m-tiles of an n-tile its
+    // W1 / dA panel) then meet in one L2 instead of fetching the panel once per XCD.
+    uint32_t bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    {
+        const uint32_t total = gridDim.x * gridDim.y * gridDim.z;
+        if (total % kXcds == 0) {
+            const uint32_t linear = bx + gridDim.x * (by + gridDim.y * bz);
+            const uint32_t logical = (linear % kXcds) * (total / kXcds) + linear / kXcds;
+            bx = logical % gridDim.x;
+            by = (logical / gridDim.x) % gridDim.y;
+            bz = logical / (gridDim.x * gridDim.y);
+        }
+    }
+    const uint32_t worker = bz;
+    const uint32_t m0 = by * BM, n0 = bx * BN;
     const Offsets o = offsets_of(p);
     const uint32_t t = threadIdx.x;
     const uint32_t ldb = p.n_hid;
@@ -113,6 +129,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     constexpr int A_QUADS = BM * kBK / 4, PA = A_QUADS / THREADS;
     constexpr int B_QUADS = kBK * BN / 4, PB = B_QUADS / THREADS;
     static_assert(PA * THREADS == A_QUADS && PB * THREADS == B_QUADS, "tile must split evenly over the block");
+    static_assert(EPI != kFwd || (PA <= 2 && PB <= 4), "the forward loop spreads the staging traffic over fixed slots of the MFMA chain");
     constexpr int A_MINOR = (EPI == kFwd) ? kBK / 4 : BM / 4;   // quads along the contiguous direction
     constexpr int A_MAJOR_PER_PASS = THREADS / A_MINOR;
     constexpr int B_K_PER_PASS = THREADS / (BN / 4);
@@ -134,11 +151,12 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     }
     b_src += static_cast<uint64_t>(b_k) * ldb + n0 + b_n;
 
-    // Forward product: two sets of staging registers, so global loads run two K slices ahead of their
+    // Forward product: four sets of staging registers, so global loads run four K slices ahead of their
     // use; that covers the HBM latency of the weight stream (one slice of MFMAs is shorter than it).
+    // One block of 8 waves per CU leaves 256 registers per lane: the sets cost nothing in occupancy.
     // Backward product: K is only the batch (4 slices); one set keeps the registers, and with them
     // the number of resident blocks, where the memory-bound epilogue wants them.
-    constexpr int NSETS = (EPI == kFwd) ? 2 : 1;
+    constexpr int NSETS = (EPI == kFwd) ? 4 : 1;
     f4 ra[NSETS][PA], rb[NSETS][PB];
     auto load_slice = [&](auto set, uint32_t slice) {
         constexpr int S = decltype(set)::value;
@@ -170,11 +188,13 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     const uint32_t frag_m = wm * 32 + lane % 32, frag_k = lane / 32, frag_n = wn * 32 + lane % 32;
     f16v acc = {0};
 
-    // Backward product: the epilogue updates this block's tile of W1 and its momentum.
-    // Their loads are issued now, so the memory latency hides behind the whole K loop.
+    // Backward product: the epilogue updates this block's tile of W1 and its momentum.  Vector loads
+    // return in order, so these 64 KB must be the YOUNGEST loads in flight or every operand slice
+    // behind them would wait for them: they are issued right after the loads of the last K slice
+    // and land under the remaining multiplies.
     constexpr int EPI_ITERS = (BM * BN / 4) / THREADS;
     f4 x_old[EPI_ITERS], v_old[EPI_ITERS];
-    if (EPI == kBwd) {
+    auto prefetch_tile = [&]() {
         #pragma unroll
         for (int it = 0; it < EPI_ITERS; ++it) {
             const uint32_t idx = it * THREADS + t;
@@ -183,7 +203,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
             x_old[it] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.x_in + at));
             v_old[it] = p.momentum != 0.0f ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.v + at)) : f4{0.f, 0.f, 0.f, 0.f};
         }
-    }
+    };
 
     // Software pipeline over the K slices (their number is a multiple of 4 by the shape contract).
     // At the top of iteration s: slice s sits in LDS buffer s&1, visible to all waves; slice s+1
@@ -192,7 +212,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     // loads of the next slice to fetch BEFORE the chain of 16 MFMAs, so all of that runs under the
     // multiplies; one barrier per slice.
     const uint32_t n_slices = K / kBK;
-    auto iteration = [&](auto next_set, uint32_t s) {
+    auto iteration = [&](auto next_set, uint32_t s, auto stage, auto load) {
         const uint32_t cur = s & 1;
         float af[kBK / 2], bf[kBK / 2];
         #pragma unroll
@@ -200,27 +220,96 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
             af[i] = As[cur][frag_m][2 * i + frag_k];
             bf[i] = Bs[cur][2 * i + frag_k][frag_n];
         }
-        if (s + 1 < n_slices) stage_to_lds(next_set, cur ^ 1);   // buffer last read in iteration s-1, before its barrier
-        if (s + 1 + NSETS < n_slices) load_slice(next_set, s + 1 + NSETS);
+        // compile-time switches, not run-time conditions (see the forward loop)
+        if constexpr (decltype(stage)::value) stage_to_lds(next_set, cur ^ 1);   // buffer last read in iteration s-1, before its barrier
+        if constexpr (decltype(load)::value) load_slice(next_set, s + 2);
         #pragma unroll
         for (int i = 0; i < kBK / 2; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[i], acc, 0, 0, 0);
         __syncthreads();        // slice s+1 visible; everyone is done reading buffer cur
     };
     load_slice(Set0{}, 0);
-    if constexpr (NSETS == 2) {
+    if constexpr (NSETS == 4) {
+        // Forward product, one stage deeper: the fragments of slice s+1 are read from LDS during the MFMA
+        // chain of slice s (two fragment sets), so the matrix pipe does not idle while both waves of a
+        // SIMD sit in their LDS-read phase (there is one block of 8 waves per CU: nothing else to run).
+        // Top of iteration s: fragments of slice s in set s&1; slice s+1 in LDS buffer (s+1)&1, visible;
+        // slices s+2 .. s+5 in (or on their way into) the four staging sets.
+        float af2[2][kBK / 2], bf2[2][kBK / 2];
+        const uint32_t last = n_slices - 1;
+        auto read_frags = [&](auto par, uint32_t buf) {
+            constexpr int F = decltype(par)::value;
+            #pragma unroll
+            for (int i = 0; i < kBK / 2; ++i) {
+                af2[F][i] = As[buf][frag_m][2 * i + frag_k];
+                bf2[F][i] = Bs[buf][2 * i + frag_k][frag_n];
+            }
+        };
+        // slice t lives in staging set t % 4; iteration s stages slice s+2 and refills that set with slice s+6
+        auto deep_iteration = [&](auto par, auto other, auto set, uint32_t s) {
+            constexpr int F = decltype(par)::value, O = decltype(other)::value, S = decltype(set)::value;
+            // No run-time conditions in the loop body: past the end the same steps run on the last slice
+            // again and their results are never used.  (With steps under `if`, the number of loads in
+            // flight at a given point depends on the path taken, and the compiler must then wait for ALL
+            // of them before the first use of any.)
+            // Issue order: the 16 multiplies form a dependent chain (each waits 64 cycles for the one
+            // before) and a wave issues in order, so the memory instructions go INTO the gaps of the
+            // chain: after multiply i, element i of the next slice's fragments, and one piece of the
+            // staging traffic.  A scheduling fence after every group pins that order; left to itself the
+            // scheduler sinks each fragment read to its first use (which undoes the pipeline) or issues
+            // the memory instructions in one lump (then both waves of a SIMD sit in that phase together,
+            // right after the barrier, and the matrix pipe idles).
+            const uint32_t nb = (s + 1) & 1, wb = s & 1;          // buffers: next fragments from nb, slice s+2 into wb
+            const uint32_t refill = s + 6 < n_slices ? s + 6 : last;
+            #pragma unroll
+            for (int i = 0; i < kBK / 2; ++i) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af2[F][i], bf2[F][i], acc, 0, 0, 0);
+                af2[O][i] = As[nb][frag_m][2 * i + frag_k];
+                bf2[O][i] = Bs[nb][2 * i + frag_k][frag_n];
+                if (i >= 2 && i < 2 + PA) {                       // A quad of slice s+2 -> LDS (buffer last read in iteration s-1)
+                    const int a = i - 2;
+                    const uint32_t major = a_major + a * A_MAJOR_PER_PASS;
+                    #pragma unroll
+                    for (int j = 0; j < 4; ++j) As[wb][major][a_minor + j] = ra[S][a][j];
+                }
+                if (i >= 4 && i < 4 + PB) {                       // B quads of slice s+2 -> LDS
+                    const int bq = i - 4;
+                    *reinterpret_cast<f4 *>(&Bs[wb][b_k + bq * B_K_PER_PASS][b_n]) = rb[S][bq];
+                }
+                if (i >= 8 && i < 8 + PA)                         // refill the staging set: slice s+6
+                    ra[S][i - 8] = *reinterpret_cast<const f4 *>(a_src + refill * a_slice + (i - 8) * a_pass);
+                if (i >= 10 && i < 10 + PB)
+                    rb[S][i - 10] = *reinterpret_cast<const f4 *>(b_src + (static_cast<uint64_t>(refill) * kBK + static_cast<uint64_t>(i - 10) * B_K_PER_PASS) * ldb);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+        };
+        using Set2 = std::integral_constant<int, 2>;
+        using Set3 = std::integral_constant<int, 3>;
         load_slice(Set1{}, 1);
+        load_slice(Set2{}, 2);
+        load_slice(Set3{}, 3);
         stage_to_lds(Set0{}, 0);
-        load_slice(Set0{}, 2);
+        load_slice(Set0{}, 4);
         __syncthreads();
-        for (uint32_t s = 0; s < n_slices; s += 2) {
-            iteration(Set1{}, s);
-            iteration(Set0{}, s + 1);
+        read_frags(Set0{}, 0);
+        stage_to_lds(Set1{}, 1);
+        load_slice(Set1{}, 5);
+        __syncthreads();
+        for (uint32_t s = 0; s < n_slices; s += 4) {        // the slice count is a multiple of 4
+            deep_iteration(Set0{}, Set1{}, Set2{}, s);
+            deep_iteration(Set1{}, Set0{}, Set3{}, s + 1);
+            deep_iteration(Set0{}, Set1{}, Set0{}, s + 2);
+            deep_iteration(Set1{}, Set0{}, Set1{}, s + 3);
         }
     } else {
         stage_to_lds(Set0{}, 0);
         load_slice(Set0{}, 1);
         __syncthreads();
-        for (uint32_t s = 0; s < n_slices; ++s) iteration(Set0{}, s);
+        uint32_t s = 0;
+        for (; s + 2 < n_slices; ++s) iteration(Set0{}, s, std::true_type{}, std::true_type{});
+        prefetch_tile();
+        iteration(Set0{}, s, std::true_type{}, std::false_type{});
+        iteration(Set0{}, s + 1, std::false_type{}, std::false_type{});
     }
 
     // accumulators -> LDS tile.  Register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of the 32x32 block.
