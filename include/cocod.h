@@ -117,7 +117,10 @@ typedef struct cocod_config {
     uint64_t stride;               /* elements between consecutive workers; >= padded_d, multiple of 4 */
     void *compute_stream;          /* hipStream_t for Step II and line 6 (NULL = the null stream) */
     void *avg_stream;              /* hipStream_t for Step I; equal to compute_stream = no overlap */
-    uint32_t mlp_in, mlp_hidden, mlp_out, mlp_batch;   /* MLP kind: layer widths and mini-batch size */
+    uint32_t mlp_in, mlp_hidden, mlp_out, mlp_batch;   /* MLP kind: layer widths and mini-batch size.  Supported
+                                      shapes (else COCOD_ERR_UNSUPPORTED): mlp_in and mlp_batch multiples of 128,
+                                      mlp_batch <= 1024, mlp_hidden a multiple of 64, 1 <= mlp_out <= 16,
+                                      mlp_hidden * (mlp_out rounded up to odd) <= 32768 */
     uint32_t flags;                /* COCOD_FLAG_* */
 } cocod_config;
 

@@ -191,7 +191,7 @@ int validate(const cocod_config *cfg, uint64_t padded_d)
         if (!cocod::mlp_shape_supported(cfg->mlp_in, cfg->mlp_hidden, cfg->mlp_out, cfg->mlp_batch))
             return fail(nullptr, COCOD_ERR_UNSUPPORTED,
                         "MLP shape: mlp_in and mlp_batch must be multiples of 128 (batch <= 1024), mlp_hidden a "
-                        "multiple of 64, 1 <= mlp_out <= 16");
+                        "multiple of 64, 1 <= mlp_out <= 16, mlp_hidden * (mlp_out rounded up to odd) <= 32768");
     }
     return COCOD_OK;
 }

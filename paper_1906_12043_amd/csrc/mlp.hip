@@ -2,11 +2,11 @@
 // perceptron  A = X W1 + b1, H = relu(A), Z = H W2 + b2, loss = mean softmax cross-entropy,
 // on a fresh seeded mini-batch per (worker, step); all W workers advance in the same launches.
 //
-// One local step = six launches on the compute stream:
+// One local step = five launches on the compute stream:
 //   gen_batch      X and labels from the counter-based generator                 (vector ALU)
 //   gemm<FWD>      H = relu(X W1 + b1)                         [B x in] x [in x hid]   fp32 MFMA
-//   head_logits    Z = H W2 + b2, softmax, dZ = (P - onehot)/B  (one wave per sample, wave reductions)
-//   head_backprop  dA = (dZ W2^T) * [H > 0]
+//   head           Z = H W2 + b2, softmax, dZ = (P - onehot)/B, dA = (dZ W2^T) * [H > 0]
+//                  (one wave per sample, wave reductions, W2 in LDS)
 //   head_update    dW2 = H^T dZ, db2, db1 = colsum(dA); momentum-SGD update of W2, b2, b1
 //   gemm<BWD>      dW1 = X^T dA with the momentum-SGD update of W1 fused into the epilogue
 //                  (the 12.6 MB gradient of W1 never goes to memory)   [in x B] x [B x hid]  fp32 MFMA
@@ -25,6 +25,7 @@
 #include "philox.hpp"
 
 #include <type_traits>
+#include <utility>
 
 namespace cocod {
 namespace {
@@ -357,117 +358,204 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// One wave per sample: logits by a strided dot product over the hidden units and a butterfly
-// reduction, then softmax (row maximum subtracted) and dZ = (P - onehot(y)) / batch.
-__global__ __launch_bounds__(256) void head_logits_kernel(const MlpParams p)
+// Output layer, forward and backward, one wave per sample (two samples per wave, eight per block):
+//   Z = H W2 + b2 by a strided dot product over the hidden units and a butterfly reduction, softmax
+//   (row maximum subtracted), dZ = (P - onehot(y)) / batch, then dA = (dZ W2^T) * [H > 0] for the
+//   wave's own hidden units.  W2 of the block's worker sits in LDS (row pitch n_out + 1 when n_out
+//   is even, so the 64 lanes of a wave, which read 64 consecutive rows, spread over the banks).
+//   The output width is a template parameter: with it known, the loops over the classes unroll into
+//   straight-line code (as a run-time bound they became a branch per class and per hidden unit).
+constexpr int kHeadSamples = 8;        // per block of 4 waves
+constexpr int kHeadBatch = 8;          // independent loads in flight per lane
+constexpr uint32_t kHeadLdsBytes = 128u << 10;
+__host__ __device__ inline uint32_t head_w2_pitch(uint32_t n_out) { return n_out % 2 == 0 ? n_out + 1 : n_out; }
+template <int NOUT>
+__global__ __launch_bounds__(256) void head_kernel(const MlpParams p)
 {
+    constexpr uint32_t w2_pitch = NOUT % 2 == 0 ? NOUT + 1 : NOUT;
+    extern __shared__ float w2s[];     // [n_hid][w2_pitch]
     const uint32_t worker = blockIdx.y;
-    const uint32_t b = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
-    if (b >= p.batch) return;
+    const uint32_t lane = threadIdx.x % 64, wave = threadIdx.x / 64;
     const Offsets o = offsets_of(p);
     const float *theta = p.x_in + static_cast<uint64_t>(worker) * p.stride;
-    const float *Hrow = p.H + (static_cast<uint64_t>(worker) * p.batch + b) * p.n_hid;
-    float z[kMaxOut];
-    #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c) z[c] = 0.0f;
-    for (uint32_t n = lane; n < p.n_hid; n += 64) {
-        const float hv = Hrow[n];
-        const float *w2 = theta + o.W2 + static_cast<uint64_t>(n) * p.n_out;
+    // W2 -> LDS in 16-byte pieces, four loads in flight per thread (the matrix starts on a 16-byte
+    // boundary and holds a multiple of 4 elements, by the shape contract)
+    const uint32_t n_quads = p.n_hid * NOUT / 4;
+    for (uint32_t q0 = threadIdx.x; q0 < n_quads; q0 += 256 * 4) {
+        f4 r[4];
         #pragma unroll
-        for (int c = 0; c < kMaxOut; ++c)
-            if (c < static_cast<int>(p.n_out)) z[c] += hv * w2[c];
+        for (int u = 0; u < 4; ++u)
+            r[u] = q0 + 256 * u < n_quads ? *reinterpret_cast<const f4 *>(theta + o.W2 + 4ull * (q0 + 256 * u)) : f4{0.f, 0.f, 0.f, 0.f};
+        #pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (q0 + 256 * u < n_quads) {
+                #pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t i = 4 * (q0 + 256 * u) + j;
+                    w2s[(i / NOUT) * w2_pitch + i % NOUT] = r[u][j];
+                }
+            }
     }
-    float zmax = -INFINITY;
-    #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c)
-        if (c < static_cast<int>(p.n_out)) {
+    __syncthreads();
+    const float inv_b = 1.0f / static_cast<float>(p.batch);
+    for (uint32_t j = 0; j < kHeadSamples / 4; ++j) {
+        const uint32_t b = blockIdx.x * kHeadSamples + wave * (kHeadSamples / 4) + j;
+        if (b >= p.batch) break;                                   // wave-uniform
+        const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b;
+        const float *Hrow = p.H + sample * p.n_hid;
+        float z[NOUT];
+        #pragma unroll
+        for (int c = 0; c < NOUT; ++c) z[c] = 0.0f;
+        // the wave's hidden units in batches of kHeadBatch loads in flight (one load at a time would
+        // make the loop a chain of memory latencies)
+        for (uint32_t n0 = lane; n0 < p.n_hid; n0 += 64 * kHeadBatch) {
+            float hv[kHeadBatch];
+            #pragma unroll
+            for (int u = 0; u < kHeadBatch; ++u) hv[u] = n0 + 64 * u < p.n_hid ? Hrow[n0 + 64 * u] : 0.0f;
+            #pragma unroll
+            for (int u = 0; u < kHeadBatch; ++u) {
+                if (n0 + 64 * u < p.n_hid) {
+                    const float *w2 = w2s + (n0 + 64 * u) * w2_pitch;
+                    #pragma unroll
+                    for (int c = 0; c < NOUT; ++c) z[c] += hv[u] * w2[c];
+                }
+            }
+        }
+        float zmax = -INFINITY;
+        #pragma unroll
+        for (int c = 0; c < NOUT; ++c) {
             z[c] = wave_sum(z[c]) + theta[o.b2 + c];
             zmax = fmaxf(zmax, z[c]);
         }
-    float denom = 0.0f;
-    #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c)
-        if (c < static_cast<int>(p.n_out)) { z[c] = expf(z[c] - zmax); denom += z[c]; }
-    const int label = p.y[static_cast<uint64_t>(worker) * p.batch + b];
-    const float inv_b = 1.0f / static_cast<float>(p.batch);
-    #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c)
-        if (c < static_cast<int>(p.n_out) && lane == static_cast<uint32_t>(c))
-            p.dZ[(static_cast<uint64_t>(worker) * p.batch + b) * kMaxOut + c] =
-                (z[c] / denom - (label == c ? 1.0f : 0.0f)) * inv_b;
-}
-
-// dA[b][n] = (sum_c dZ[b][c] W2[n][c]) * [H[b][n] > 0]; a thread owns hidden unit n for 8 samples.
-__global__ __launch_bounds__(256) void head_backprop_kernel(const MlpParams p)
-{
-    const uint32_t worker = blockIdx.z;
-    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= p.n_hid) return;
-    const Offsets o = offsets_of(p);
-    const float *w2 = p.x_in + static_cast<uint64_t>(worker) * p.stride + o.W2 + static_cast<uint64_t>(n) * p.n_out;
-    float w[kMaxOut];
-    #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c) w[c] = c < static_cast<int>(p.n_out) ? w2[c] : 0.0f;
-    for (uint32_t b = blockIdx.y * 8; b < blockIdx.y * 8 + 8 && b < p.batch; ++b) {
-        const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b;
-        const float *dz = p.dZ + sample * kMaxOut;
-        float dh = 0.0f;
+        float denom = 0.0f;
         #pragma unroll
-        for (int c = 0; c < kMaxOut; ++c)
-            if (c < static_cast<int>(p.n_out)) dh += dz[c] * w[c];
-        p.dA[sample * p.n_hid + n] = p.H[sample * p.n_hid + n] > 0.0f ? dh : 0.0f;
+        for (int c = 0; c < NOUT; ++c) { z[c] = expf(z[c] - zmax); denom += z[c]; }
+        const int label = p.y[sample];
+        #pragma unroll
+        for (int c = 0; c < NOUT; ++c) {
+            z[c] = (z[c] / denom - (label == c ? 1.0f : 0.0f)) * inv_b;                // dZ, the same in every lane
+            if (lane == static_cast<uint32_t>(c)) p.dZ[sample * kMaxOut + c] = z[c];
+        }
+        for (uint32_t n0 = lane; n0 < p.n_hid; n0 += 64 * kHeadBatch) {
+            float hv[kHeadBatch];
+            #pragma unroll
+            for (int u = 0; u < kHeadBatch; ++u) hv[u] = n0 + 64 * u < p.n_hid ? Hrow[n0 + 64 * u] : 0.0f;
+            #pragma unroll
+            for (int u = 0; u < kHeadBatch; ++u) {
+                if (n0 + 64 * u < p.n_hid) {
+                    const float *w2 = w2s + (n0 + 64 * u) * w2_pitch;
+                    float dh = 0.0f;
+                    #pragma unroll
+                    for (int c = 0; c < NOUT; ++c) dh += z[c] * w2[c];
+                    p.dA[sample * p.n_hid + n0 + 64 * u] = hv[u] > 0.0f ? dh : 0.0f;
+                }
+            }
+        }
     }
 }
 
 // Gradients of the small parameters and their update.  A block owns 64 hidden units (row n of W2 and
 // b1[n]); its four waves each sum a quarter of the batch and the partial sums meet in LDS in a fixed
 // order.  Block 0 of a worker also owns b2 and the alignment pads.
+template <int NOUT>
 __global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
 {
-    __shared__ float part[4][64][kMaxOut + 1];
+    __shared__ float part[4][64][NOUT + 1];
     const uint32_t worker = blockIdx.y;
     const uint32_t u = threadIdx.x % 64, slice = threadIdx.x / 64;
     const uint32_t n = blockIdx.x * 64 + u;
     const Offsets o = offsets_of(p);
     const uint64_t base = static_cast<uint64_t>(worker) * p.stride;
-    float gw[kMaxOut];
+    float gw[NOUT];
     #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c) gw[c] = 0.0f;
+    for (int c = 0; c < NOUT; ++c) gw[c] = 0.0f;
     float gb = 0.0f;
     if (n < p.n_hid) {
-        const uint32_t per = p.batch / 4;
-        for (uint32_t b = slice * per; b < (slice + 1) * per; ++b) {
-            const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b;
-            const float hv = p.H[sample * p.n_hid + n];
-            gb += p.dA[sample * p.n_hid + n];
-            const float *dz = p.dZ + sample * kMaxOut;
+        const uint32_t per = p.batch / 4;                            // a multiple of 32 by the shape contract
+        for (uint32_t b0 = slice * per; b0 < (slice + 1) * per; b0 += kHeadBatch) {
+            float hv[kHeadBatch], da[kHeadBatch];                    // the batch's loads are all in flight together
             #pragma unroll
-            for (int c = 0; c < kMaxOut; ++c)
-                if (c < static_cast<int>(p.n_out)) gw[c] += hv * dz[c];
+            for (int j = 0; j < kHeadBatch; ++j) {
+                const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b0 + j;
+                hv[j] = p.H[sample * p.n_hid + n];
+                da[j] = p.dA[sample * p.n_hid + n];
+            }
+            #pragma unroll
+            for (int j = 0; j < kHeadBatch; ++j) {
+                gb += da[j];
+                const float *dz = p.dZ + (static_cast<uint64_t>(worker) * p.batch + b0 + j) * kMaxOut;
+                #pragma unroll
+                for (int c = 0; c < NOUT; ++c) gw[c] += hv[j] * dz[c];
+            }
         }
     }
     #pragma unroll
-    for (int c = 0; c < kMaxOut; ++c) part[slice][u][c] = gw[c];
-    part[slice][u][kMaxOut] = gb;
+    for (int c = 0; c < NOUT; ++c) part[slice][u][c] = gw[c];
+    part[slice][u][NOUT] = gb;
     __syncthreads();
     if (slice == 0 && n < p.n_hid) {
+        // row n of W2 and b1[n]: all old values first (independent loads), then the updates
+        uint64_t at[NOUT + 1];
+        float xo[NOUT + 1], vo[NOUT + 1];
         #pragma unroll
-        for (int c = 0; c < kMaxOut; ++c)
-            if (c < static_cast<int>(p.n_out))
-                sgd_update(p, base + o.W2 + static_cast<uint64_t>(n) * p.n_out + c,
-                           ((part[0][u][c] + part[1][u][c]) + part[2][u][c]) + part[3][u][c]);
-        sgd_update(p, base + o.b1 + n, ((part[0][u][kMaxOut] + part[1][u][kMaxOut]) + part[2][u][kMaxOut]) + part[3][u][kMaxOut]);
+        for (int c = 0; c <= NOUT; ++c) {
+            at[c] = c == NOUT ? base + o.b1 + n : base + o.W2 + static_cast<uint64_t>(n) * NOUT + c;
+            xo[c] = p.x_in[at[c]];
+            vo[c] = p.momentum != 0.0f ? p.v[at[c]] : 0.0f;
+        }
+        #pragma unroll
+        for (int c = 0; c <= NOUT; ++c) {
+            {
+                const float G = ((part[0][u][c] + part[1][u][c]) + part[2][u][c]) + part[3][u][c];
+                float g = G + p.weight_decay * xo[c];
+                if (p.momentum != 0.0f) {
+                    g = p.momentum * vo[c] + g;
+                    p.v[at[c]] = g;
+                }
+                p.x_out[at[c]] = xo[c] - p.lr * g;
+            }
+        }
     }
     if (blockIdx.x == 0 && slice == 1) {
-        if (u < p.n_out) {
-            float g = 0.0f;
-            for (uint32_t b = 0; b < p.batch; ++b)
-                g += p.dZ[(static_cast<uint64_t>(worker) * p.batch + b) * kMaxOut + u];
-            sgd_update(p, base + o.b2 + u, g);
+        // db2[c] = sum_b dZ[b][c]: lanes take the samples 64 apart, then a butterfly over the wave
+        float col[NOUT];
+        #pragma unroll
+        for (int c = 0; c < NOUT; ++c) col[c] = 0.0f;
+        for (uint32_t b = u; b < p.batch; b += 64) {
+            const float *dz = p.dZ + (static_cast<uint64_t>(worker) * p.batch + b) * kMaxOut;
+            #pragma unroll
+            for (int c = 0; c < NOUT; ++c) col[c] += dz[c];
         }
-        const uint64_t d = o.b2 + p.n_out;                       // pads after the last parameter travel along
+        #pragma unroll
+        for (int c = 0; c < NOUT; ++c) {
+            const float g = wave_sum(col[c]);
+            if (u == static_cast<uint32_t>(c)) sgd_update(p, base + o.b2 + u, g);
+        }
+        const uint64_t d = o.b2 + NOUT;                       // pads after the last parameter travel along
         if (p.x_out != p.x_in && u < ((d + 3) & ~3ull) - d) p.x_out[base + d + u] = p.x_in[base + d + u];
     }
+}
+
+// The two output-layer kernels, instantiated for every supported output width 1..kMaxOut.
+template <int NOUT>
+hipError_t launch_heads_for(hipStream_t stream, const MlpParams &p)
+{
+    // more than the default 64 KB of dynamic LDS for wide hidden layers
+    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(head_kernel<NOUT>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, kHeadLdsBytes);
+    if (lds_ok != hipSuccess) return lds_ok;
+    hipLaunchKernelGGL(head_kernel<NOUT>, dim3((p.batch + kHeadSamples - 1) / kHeadSamples, p.W), dim3(256),
+                       static_cast<size_t>(p.n_hid) * head_w2_pitch(NOUT) * sizeof(float), stream, p);
+    hipLaunchKernelGGL(head_update_kernel<NOUT>, dim3((p.n_hid + 63) / 64, p.W), dim3(256), 0, stream, p);
+    return hipSuccess;
+}
+
+template <int... I>
+hipError_t launch_heads(hipStream_t stream, const MlpParams &p, std::integer_sequence<int, I...>)
+{
+    hipError_t rc = hipErrorInvalidValue;
+    (void)((p.n_out == static_cast<uint32_t>(I + 1) ? (rc = launch_heads_for<I + 1>(stream, p), true) : false) || ...);
+    return rc;
 }
 
 }  // namespace
@@ -476,7 +564,8 @@ bool mlp_shape_supported(uint32_t n_in, uint32_t n_hid, uint32_t n_out, uint32_t
 {
     return n_in >= static_cast<uint32_t>(kShapeM) && n_in % kShapeM == 0 && n_hid >= static_cast<uint32_t>(kShapeN) &&
            n_hid % kShapeN == 0 && n_out >= 1 && n_out <= static_cast<uint32_t>(kMaxOut) &&
-           batch >= static_cast<uint32_t>(kShapeM) && batch % kShapeM == 0 && batch <= 1024;
+           batch >= static_cast<uint32_t>(kShapeM) && batch % kShapeM == 0 && batch <= 1024 &&
+           static_cast<uint64_t>(n_hid) * head_w2_pitch(n_out) * sizeof(float) <= kHeadLdsBytes;   // W2 lives in LDS
 }
 
 size_t mlp_dz_pitch() { return kMaxOut; }
@@ -487,9 +576,8 @@ hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
     const bool wide = p.n_hid % 128 == 0;      // 64 x 128 block tiles (fastest measured), else 64 x 64
     hipLaunchKernelGGL(gen_batch_kernel, dim3(static_cast<uint32_t>((n_quads + 255) / 256), p.W), dim3(256), 0, stream, p);
     if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
-    hipLaunchKernelGGL(head_logits_kernel, dim3((p.batch + 3) / 4, p.W), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(head_backprop_kernel, dim3((p.n_hid + 255) / 256, (p.batch + 7) / 8, p.W), dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(head_update_kernel, dim3((p.n_hid + 63) / 64, p.W), dim3(256), 0, stream, p);
+    const hipError_t head_rc = launch_heads(stream, p, std::make_integer_sequence<int, kMaxOut>{});
+    if (head_rc != hipSuccess) return head_rc;
     if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p);
     return hipGetLastError();
 }
