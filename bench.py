@@ -187,8 +187,13 @@ def bench_mlp(args):
     ctx = P.Context(W=W, d=d, stride=stride, xA=xA, xB=xB, v=v, mean=mean, grad=P.GRAD_MLP, mlp=(*shape, batch),
                     lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"],
                     compute_stream=s_compute, avg_stream=s_avg)
-    per_round, step_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "separate")
-    graph_round, _, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "graph_separate")
+    fused = args.variant == "fused_tail"
+    per_round, plain_s, tail_s = time_rounds(ctx, torch, k, args.steps, args.warmup, args.variant)
+    # average local step over the round: k-1 plain steps and one that also applies line 6, or k plain ones
+    step_s = ((plain_s or 0.0) * (k - 1) + tail_s) / k if fused else plain_s
+    other = "separate" if fused else "fused_tail"
+    other_round, _, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, other, False)
+    graph_round, _, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "graph_" + args.variant)
     n_in, n_hid, n_out = shape
     gemm_flops = W * 2 * (2 * batch * n_in * n_hid)
     all_flops = gemm_flops + W * 3 * (2 * batch * n_hid * n_out)
@@ -199,11 +204,14 @@ def bench_mlp(args):
         "warmup": args.warmup, "ms_per_step": per_round * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C4 MLP workers 3072-1024-10, batch 128 fresh N(0,1) inputs per worker-step, momentum 0.9, "
-                               "lr 0.05", "k": k, "W": W, "d": d, "variant": "separate"},
+                               "lr 0.05", "k": k, "W": W, "d": d, "variant": args.variant},
         "local_step_ms": step_s * 1e3,
+        "plain_step_ms": plain_s * 1e3 if plain_s else None,
+        "line6_step_ms": tail_s * 1e3 if tail_s else None,
+        other + "_ms_per_round": other_round * 1e3,
         "graph_ms_per_round": graph_round * 1e3,
         "local_step_TFLOPs_all": all_flops / step_s / 1e12,
-        "roofline": {"bound": "mfma", "kernel": "one local step (6 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
+        "roofline": {"bound": "mfma", "kernel": "one local step (5 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
                      "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": step_s * 1e3,
                      "launches_timed": args.steps * k, "algorithmic_flops_per_launch": gemm_flops},

@@ -390,12 +390,14 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
         p.step_base = ctx->capturing ? ctx->d_step : nullptr;
+        p.snap = with_line6 ? ctx->snap : nullptr;
+        p.mean = ctx->cfg.mean;
         const bool timed = ctx->timing && ctx->t_used < ctx->t_start.size();
         if (timed) COCOD_HIP(ctx, hipEventRecord(ctx->t_start[ctx->t_used], ctx->s_compute));
         COCOD_HIP(ctx, cocod::launch_mlp_step(ctx->s_compute, p));
         if (timed) {
             COCOD_HIP(ctx, hipEventRecord(ctx->t_stop[ctx->t_used], ctx->s_compute));
-            ctx->t_kind[ctx->t_used] = 0;
+            ctx->t_kind[ctx->t_used] = with_line6 ? 1 : 0;
             ctx->t_used += 1;
         }
     } else if (!ctx->dry) {
@@ -513,10 +515,6 @@ int cocod_local_steps_end_apply(cocod_ctx *ctx, int k)
     if (k == 0) return cocod_average_end_apply(ctx);
     rc = need_builtin_gradient(ctx);
     if (rc != COCOD_OK) return rc;
-    if (ctx->cfg.grad == COCOD_GRAD_MLP) {      // the MLP step has no line-6 epilogue: separate kernel
-        for (int s = 0; s < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
-        return rc == COCOD_OK ? cocod_average_end_apply(ctx) : rc;
-    }
     for (int s = 0; s + 1 < k && rc == COCOD_OK; ++s) rc = enqueue_step(ctx, false);
     if (rc != COCOD_OK) return rc;
     if (!ctx->dry) {

@@ -86,6 +86,8 @@ struct MlpParams {
     float lr, momentum, weight_decay;
     uint32_t key0, key1, step;
     const uint32_t *step_base;   // as in StepParams
+    const float *snap;        // non-null: last step of a round; line 6 is applied to every updated parameter
+    const float *mean;        //           before it is stored: x = mean + (x_new - snap)   (mean is [stride])
     // work space owned by the context
     float *X;                 // [W][batch][n_in]
     float *H;                 // [W][batch][n_hid]  relu output

@@ -59,7 +59,9 @@ __device__ __forceinline__ void sgd_update(const MlpParams &p, uint64_t at, floa
         p.v[at] = v;
         g = v;
     }
-    p.x_out[at] = x - p.lr * g;
+    float x_new = x - p.lr * g;
+    if (p.snap) x_new = p.mean[at % p.stride] + (x_new - p.snap[at]);     // line 6 (last step of a round)
+    p.x_out[at] = x_new;
 }
 
 // ---- mini-batch ---------------------------------------------------------------------------------
@@ -86,7 +88,7 @@ __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
 }
 
 // ---- the two big contractions ---------------------------------------------------------------------
-enum { kFwd = 0, kBwd = 1 };
+enum { kFwd = 0, kBwd = 1, kBwdTail = 2 };   // kBwdTail: the backward product of a round's last step (line 6 in its epilogue)
 constexpr uint32_t kXcds = 8;      // accelerator complex dies of the MI355X
 
 // NWM x NWN waves per block, one 32x32 accumulator per wave: block tile (32 NWM) x (32 NWN).
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     // behind them would wait for them: they are issued right after the loads of the last K slice
     // and land under the remaining multiplies.
     constexpr int EPI_ITERS = (BM * BN / 4) / THREADS;
-    f4 x_old[EPI_ITERS], v_old[EPI_ITERS];
+    f4 x_old[EPI_ITERS], v_old[EPI_ITERS], snap_old[EPI_ITERS];
     auto prefetch_tile = [&]() {
         #pragma unroll
         for (int it = 0; it < EPI_ITERS; ++it) {
@@ -203,6 +205,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
                                 static_cast<uint64_t>(m0 + idx / (BN / 4)) * p.n_hid + n0 + (idx % (BN / 4)) * 4;
             x_old[it] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.x_in + at));
             v_old[it] = p.momentum != 0.0f ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.v + at)) : f4{0.f, 0.f, 0.f, 0.f};
+            if (EPI == kBwdTail) snap_old[it] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p.snap + at));
         }
     };
 
@@ -338,7 +341,12 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
                 g = p.momentum * v_old[it] + g;
                 __builtin_nontemporal_store(g, reinterpret_cast<f4 *>(p.v + at));
             }
-            __builtin_nontemporal_store(x_old[it] - p.lr * g, reinterpret_cast<f4 *>(p.x_out + at));
+            f4 x_new = x_old[it] - p.lr * g;
+            if (EPI == kBwdTail) {       // line 6 of Algorithm 1 on the fresh model, same operation order as the separate kernel
+                const f4 mean = *reinterpret_cast<const f4 *>(p.mean + o.W1 + static_cast<uint64_t>(m0 + row) * p.n_hid + n0 + col);
+                x_new = mean + (x_new - snap_old[it]);
+            }
+            __builtin_nontemporal_store(x_new, reinterpret_cast<f4 *>(p.x_out + at));
         }
     }
 }
@@ -512,7 +520,9 @@ __global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
                     g = p.momentum * vo[c] + g;
                     p.v[at[c]] = g;
                 }
-                p.x_out[at[c]] = xo[c] - p.lr * g;
+                float x_new = xo[c] - p.lr * g;
+                if (p.snap) x_new = p.mean[at[c] - base] + (x_new - p.snap[at[c]]);   // line 6 (last step of a round)
+                p.x_out[at[c]] = x_new;
             }
         }
     }
@@ -578,7 +588,8 @@ hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
     if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
     const hipError_t head_rc = launch_heads(stream, p, std::make_integer_sequence<int, kMaxOut>{});
     if (head_rc != hipSuccess) return head_rc;
-    if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p);
+    if (p.snap) { if (wide) launch_gemm<kBwdTail, 2, 4>(stream, p); else launch_gemm<kBwdTail, 2, 2>(stream, p); }
+    else        { if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p); }
     return hipGetLastError();
 }
 

@@ -115,6 +115,27 @@ def test_small_networks_rounds(W, shape, batch, k):
     g.close()
 
 
+@pytest.mark.parametrize("W,shape,batch", [(3, (128, 64, 10), 128), (2, (256, 192, 3), 256), (2, (128, 128, 16), 128)])
+def test_line6_inside_the_last_step_gives_the_same_bits(W, shape, batch):
+    """cocod_local_steps_end_apply applies line 6 in the update epilogues of the round's last step; the
+    result must equal cocod_local_steps + cocod_average_end_apply bit for bit, for k = 1 (the step reads
+    the stored models), 2, 3 and 0, under each schedule, and follow the oracle."""
+    theta0 = synth_inputs.mlp_he_init(5, *shape)
+    a, b = GpuMlp(W, shape, batch, theta0, **HYPER), GpuMlp(W, shape, batch, theta0, **HYPER)
+    o = mlp.MlpOracle(theta0, W, *shape, batch, **HYPER)
+    for k, sched in [(2, P.SCHED_OVERLAP), (1, P.SCHED_OVERLAP), (3, P.SCHED_SERIAL), (0, P.SCHED_OVERLAP), (2, P.SCHED_FUSED),
+                     (1, P.SCHED_HEAD)]:
+        for w in (a, b):
+            w.ctx.set_schedule(sched)
+        a.ctx.round(k)
+        b.ctx.average_begin(); b.ctx.local_steps_end_apply(k)
+        o.round(k)
+        assert np.array_equal(a.x(), b.x()) and np.array_equal(a.vel(), b.vel()), (k, sched)
+        assert not b.ctx.is_averaging() and a.ctx.get_step() == b.ctx.get_step() == o.step
+    assert rel_err(b.x(), o.x) <= TOL and rel_err(b.vel(), o.v) <= TOL
+    a.close(); b.close()
+
+
 def test_mlp_shape_validation():
     dev = torch.device("cuda:0")
     for shape, batch in [((100, 64, 10), 128), ((128, 60, 10), 128), ((128, 64, 17), 128), ((128, 64, 10), 100)]:
