@@ -283,3 +283,17 @@ def test_diagnostics_on_dry_contexts():
         with pytest.raises(P.CocodError) as e:
             ctx.quadratic_objective()
         assert e.value.status == P.ERR_INVALID
+
+
+def test_launch_size_limits():
+    """One block per (chunk of 1024 elements, worker): the product must fit a launch."""
+    with pytest.raises(P.CocodError) as e:
+        dry(W=65535, d=2**34 - 4)
+    assert e.value.status == P.ERR_INVALID and "too large" in str(e.value)
+    with pytest.raises(P.CocodError) as e:
+        dry(W=2048, d=2**30 + 1024)                       # 2^20 + 1 chunks x 2^11 workers > 2^31 - 1
+    assert e.value.status == P.ERR_INVALID
+    with dry(W=2047, d=2**30) as ctx:                      # 2^20 chunks x 2047 workers: fits
+        assert ctx.get_plan() == (2**30, 2**20, 1)
+        ctx.round(2)
+        ctx.round_fused_tail(1)
