@@ -29,7 +29,8 @@ def edge_columns(d, starts=()):
     return edges
 
 
-def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, stable_rounds=None, fused_tail=False):
+def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, stable_rounds=None, fused_tail=False,
+                  graph=False, schedule=None):
     """Runs cfg["rounds"] rounds on the GPU (full size) and in the oracle (sampled columns).
 
     stable_rounds: for an iteration whose round map is expanding (see the k = 8 case below) the
@@ -45,8 +46,12 @@ def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, s
     assert np.array_equal(hg, h) and np.max(np.abs(cg.astype(np.float64) - c)) < 2e-6
     o = orc.QuadraticOracle(h, c, idx=cols, **hyper_of(cfg))
     mirror = orc.QuadraticOracle(h, c, idx=cols, kind="f32", **hyper_of(cfg)) if stable_rounds else None
+    if schedule is not None:
+        g.ctx.set_schedule(schedule)
     for r in range(cfg["rounds"]):
-        if fused_tail:
+        if graph:
+            g.ctx.graph_round(k, fused_tail)   # the round replayed from a HIP graph
+        elif fused_tail:
             g.ctx.round_fused_tail(k)          # line 6 inside the last local step (the benchmark's variant)
         else:
             g.ctx.round(k)
@@ -99,6 +104,19 @@ def test_resnet18_size_fifty_rounds_sampled_line6_in_last_step(k):
 
 def bucketed_sizes(cfg):
     return synth_inputs.tensor_sizes(cfg["seed"], cfg["n_tensors"], cfg["d"], cfg["tensor_lo"], cfg["tensor_hi"])
+
+
+@pytest.mark.parametrize("graph,schedule", [(True, None), (False, P.SCHED_HEAD), (True, P.SCHED_HEAD)])
+def test_resnet18_size_fifty_rounds_sampled_graph_and_head_schedule(graph, schedule):
+    """The benchmark's other launch configurations at full size: rounds replayed from a graph, and the
+    mean formed inside the first local step."""
+    subset_parity(synth_inputs.CONFIGS["C2_resnet18"], 2, fused_tail=True, graph=graph, schedule=schedule)
+
+
+def test_bucketed_tensor_list_sampled_head_schedule_from_graph():
+    cfg = synth_inputs.CONFIGS["C5_bucketed"]
+    subset_parity(cfg, 2, tensor_numel=bucketed_sizes(cfg), bucket_bytes=cfg["bucket_bytes"], fused_tail=True, graph=True,
+                  schedule=P.SCHED_HEAD)
 
 
 @pytest.mark.parametrize("k,fused_tail", [(1, False), (2, False), (4, False), (2, True)])
