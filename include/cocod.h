@@ -20,8 +20,9 @@
  *     the GPU except cocod_sync, cocod_step_timing_read and cocod_destroy
  *     (cocod_create copies its small tables synchronously).
  *   - the caller owns all large device buffers and both streams; they must
- *     outlive the context.  The context owns its chunk table, two events, the
- *     optional weight vector and the MLP work space.
+ *     outlive the context.  The context owns its small tables (chunk table, weight and
+ *     noise-scale vectors), two events, the MLP work space, the scratch of the
+ *     diagnostics, and the recorded graphs with their step-counter word.
  *   - argument errors are detected before any GPU call is made.
  *   - a context is not thread safe; use it from one host thread at a time.
  */
