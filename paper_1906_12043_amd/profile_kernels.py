@@ -54,6 +54,10 @@ def main(reps=5):
     for _ in range(reps):                       # k = 1: the step with line 6 reads the stored models as its input
         ctx.round_fused_tail(1)
     ctx.sync()
+    ctx.set_schedule(P.SCHED_HEAD)              # the mean formed inside the round's first step (column-wise step kernel)
+    for _ in range(reps):
+        ctx.round_fused_tail(2)
+    ctx.sync()
     ctx.close()
     print("profile_kernels: done, W=%d d=%d stride=%d reps=%d" % (W, d, stride, reps))
 
