@@ -183,14 +183,15 @@ def test_overlapped_round_is_bit_identical_to_serialised_rounds():
         assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]), (schedule, two)
 
 
-@pytest.mark.parametrize("weights", [None, [0.1, 0.2, 0.3, 0.15, 0.25]])
-def test_mean_formed_inside_the_first_step_gives_the_same_bits(weights):
+@pytest.mark.parametrize("weights,mu,sigma", [(None, 0.9, 0.01), ([0.1, 0.2, 0.3, 0.15, 0.25], 0.9, 0.01), (None, 0.0, 0.01),
+                                              ([0.1, 0.2, 0.3, 0.15, 0.25], 0.0, 0.0), (None, 0.9, 0.0)])
+def test_mean_formed_inside_the_first_step_gives_the_same_bits(weights, mu, sigma):
     """COCOD_SCHED_HEAD against the two-stream schedule: packed list with every start alignment, k = 0
     (no step to ride on), 1 (first step is the last), 2, 3, both ways of applying line 6, mean included."""
     W = 5
     sizes = [5, 4096, 1, 3, 8191, 64, 4097, 2, 3000, 7]
     d = sum(sizes)
-    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=78, weights=weights)
+    hyper = dict(lr=0.05, momentum=mu, weight_decay=5e-4, noise_sigma=sigma, seed=78, weights=weights)
     h, c = synth_inputs.quadratic_data(16, W, d)
     a = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
     b = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)
@@ -205,7 +206,7 @@ def test_mean_formed_inside_the_first_step_gives_the_same_bits(weights):
                     w.ctx.round(k)
                 w.ctx.sync()
             o.round(k)
-            for name in ("live", "v", "mean"):
+            for name in ("live", "v", "mean") if mu else ("live", "mean"):
                 ta, tb = (getattr(w, name)() if name == "live" else getattr(w, name) for w in (a, b))
                 assert torch.equal(ta[..., a.pos], tb[..., b.pos]), (k, fused_tail, name)
     check_state(b, o, what="head schedule")
