@@ -10,8 +10,9 @@ Two ways of running the same round are timed:
   separate    cocod_average_begin; cocod_local_steps(k); cocod_average_end_apply
   fused_tail  cocod_average_begin; cocod_local_steps_end_apply(k)   (line 6 inside the last step)
 Prints ONE JSON line.  `value` = worker-param-updates/s = W*d*k / round time at k=2 for the variant
-named in config.variant; the other variant, the k sweep, the serial schedules, the roofline of the
-step kernels and the CPU oracle timed on the host cores ride along in the same line.
+named in config.variant; the k sweep (both variants, each also replayed from a HIP graph, and under
+the schedule that forms the mean inside the round's first step), the serial schedules, the roofline
+of the step kernels and the CPU oracle timed on the host cores ride along in the same line.
 """
 import argparse
 import json
@@ -55,13 +56,11 @@ def moved_round_bytes(W, d, k, variant):
     return W * d * (STEP_BYTES * (k - 1) + 4 * (1 + 1 / W)) + tail_step_bytes(W, d, k)
 
 
-LAST_HEAD_STEP_S = [None]     # average duration of the mean-forming first step in the last time_rounds call
-
-
 def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
     """Seconds per round over `rounds` timed rounds and, measured over the same rounds from the
     kernels' own start/stop timestamps on the compute stream, the average duration in seconds of the
-    plain step kernel and of the step kernel that carries line 6 (None where there was no launch)."""
+    plain step kernel, of the step kernel that carries line 6 and of the first step that also forms the
+    mean (None where there was no launch)."""
     import paper_1906_12043_amd as P
     head = variant.startswith("head_")           # Step I inside the round's first step (one stream)
     if head:
@@ -96,10 +95,9 @@ def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
             if n:
                 avg[i] = total_ms / n / 1e3
         ctx.step_timing(0)
-    LAST_HEAD_STEP_S[0] = avg[2]
     if head:
         ctx.set_schedule(P.SCHED_OVERLAP)
-    return elapsed / rounds, avg[0], avg[1]
+    return elapsed / rounds, avg[0], avg[1], avg[2]
 
 
 def timelines(ctx, torch, P, k, rounds):
@@ -188,12 +186,12 @@ def bench_mlp(args):
                     lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"],
                     compute_stream=s_compute, avg_stream=s_avg)
     fused = args.variant == "fused_tail"
-    per_round, plain_s, tail_s = time_rounds(ctx, torch, k, args.steps, args.warmup, args.variant)
+    per_round, plain_s, tail_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, args.variant)
     # average local step over the round: k-1 plain steps and one that also applies line 6, or k plain ones
     step_s = ((plain_s or 0.0) * (k - 1) + tail_s) / k if fused else plain_s
     other = "separate" if fused else "fused_tail"
-    other_round, _, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, other, False)
-    graph_round, _, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, "graph_" + args.variant)
+    other_round = time_rounds(ctx, torch, k, args.steps, args.warmup, other, False)[0]
+    graph_round = time_rounds(ctx, torch, k, args.steps, args.warmup, "graph_" + args.variant)[0]
     n_in, n_hid, n_out = shape
     gemm_flops = W * 2 * (2 * batch * n_in * n_hid)
     all_flops = gemm_flops + W * 3 * (2 * batch * n_hid * n_out)
@@ -283,7 +281,7 @@ def main():
         STEP_BYTES = 16
     traffic = STEP_TRAFFIC_BYTES if args.workload == "C2" else None
     k, variant = args.k, args.variant
-    per_round, plain_s, tail_s = time_rounds(ctx, torch, k, args.steps, args.warmup, variant)
+    per_round, plain_s, tail_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, variant)
     out = {
         "metric": "worker-param-updates/s per CoCoD round (W=%d, d=%.4gM)" % (W, d / 1e6),
         "value": W * d * k / per_round,
@@ -324,19 +322,19 @@ def main():
                      "head_graph_fused_tail"):
             sweep = {}
             for kk in cfg["k"]:
-                pr, ps, ts = time_rounds(ctx, torch, kk, args.steps, 2, name)
+                pr, ps, ts, hs = time_rounds(ctx, torch, kk, args.steps, 2, name)
                 sweep["k=%d" % kk] = {"ms_per_round": pr * 1e3, "updates_per_s": W * d * kk / pr,
                                       "model_GBps": model_round_bytes(W, d, kk) / pr / 1e9,
                                       "moved_GBps": moved_round_bytes(W, d, kk, name) / pr / 1e9,
                                       "plain_step_ms": ps * 1e3 if ps else None,
                                       "tail_step_ms": ts * 1e3 if ts else None,
-                                      "head_step_ms": LAST_HEAD_STEP_S[0] * 1e3 if LAST_HEAD_STEP_S[0] else None}
+                                      "head_step_ms": hs * 1e3 if hs else None}
             variants[name] = sweep
         out["k_sweep"] = variants
         sched = {}
         for name, code in (("serial", P.SCHED_SERIAL), ("serial_fused_mean_line6", P.SCHED_FUSED), ("overlap", P.SCHED_OVERLAP)):
             ctx.set_schedule(code)
-            pr, _, _ = time_rounds(ctx, torch, k, args.steps, 2, "separate", False)
+            pr = time_rounds(ctx, torch, k, args.steps, 2, "separate", False)[0]
             sched[name] = pr * 1e3
         out["separate_schedule_ms_per_round"] = sched
         out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, args.steps)
