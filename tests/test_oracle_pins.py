@@ -384,3 +384,57 @@ def test_external_step_hand_values_and_replay_of_logged_gradients():
             a.average_end_apply(); b.average_end_apply()
         assert np.array_equal(a.x, b.x) and a.step == b.step
         assert mu == 0.0 or np.array_equal(a.v, b.v)
+
+
+def _theorem1_sides(o, k, rounds, L, sigma2, zeta2):
+    """Runs `rounds` rounds of Algorithm 1 on oracle o (plain SGD) and returns both sides of the bound of
+    Theorem 1: (1/T) sum_t D1 ||grad f(xhat_t)||^2 over ALL iterations t (xhat_t = weighted mean of the
+    local models at iteration t), and 2 (f(xhat_0) - f*) / (T gamma) + D2 (N sigma^2 / sum M + 2 k zeta^2)
+    + gamma L sigma^2 / sum M, here with M_i = 1."""
+    gamma, T = o.lr, k * rounds
+    D2 = 8 * gamma**2 * L**2 * k / (1 - 16 * gamma**2 * k**2 * L**2)
+    D1 = 1 - 2 * k * D2
+    assert gamma <= 1 / L and D1 > 0
+    p = np.full(o.W, 1.0 / o.W)
+    hp = p[:, None] * o.h.astype(np.float64)
+    fstar = o.objective(np.sum(hp * o.c, axis=0) / np.sum(hp, axis=0))[0]
+    f0 = o.objective(p @ o.x)[0]
+    total = 0.0
+    for _ in range(rounds):
+        o.average_begin()
+        for _ in range(k):
+            grad = o.objective(p @ o.x)[1]
+            total += D1 * float(grad @ grad)
+            o.local_steps(1)
+        o.average_end_apply()
+    lhs = total / T
+    rhs = 2 * (f0 - fstar) / (T * gamma) + D2 * (o.W * sigma2 / o.W + 2 * k * zeta2) + gamma * L * sigma2 / o.W
+    return lhs, rhs
+
+
+def test_convergence_bound_of_theorem_1_holds_and_catches_a_wrong_correction():
+    """Theorem 1 on workers that satisfy its assumptions exactly: shared curvature h (so that the
+    between-worker gradient variance zeta^2 = E_i ||h (c_i - cbar)||^2 is a constant), L = max h, noise
+    of variance sigma_noise^2 per coordinate (sigma^2 = d sigma_noise^2), plain SGD, M_i = 1.  The
+    measured left-hand side must respect the bound; with line 6 applied with the wrong sign (planted in
+    a copy of the oracle's step, on the CPU) it must not."""
+    W, d, k, rounds = 4, 512, 2, 300
+    rng = np.random.default_rng(12)
+    h = np.tile(rng.uniform(0.5, 2.0, d).astype(np.float32), (W, 1))
+    c = rng.standard_normal((W, d)).astype(np.float32)
+    sn = 0.05
+    L = float(h.max())
+    dev = h[0].astype(np.float64) * (c - c.mean(axis=0))
+    zeta2 = float(np.mean(np.sum(dev * dev, axis=1)))
+    hyper = dict(lr=0.02, noise_sigma=sn, seed=99)
+    x0 = 3.0 * rng.standard_normal(d)
+    lhs, rhs = _theorem1_sides(orc.QuadraticOracle(h, c, x0, **hyper), k, rounds, L, d * sn * sn, zeta2)
+    assert 0 < lhs <= rhs, (lhs, rhs)
+    assert lhs > 0.02 * rhs                       # the bound is not vacuous at this horizon
+
+    class WrongSign(orc.QuadraticOracle):
+        def average_end_apply(self):
+            self.x[...] = self.mean[None, :] - (self.x - self.snap)
+            self.averaging = False
+    bad_lhs, bad_rhs = _theorem1_sides(WrongSign(h, c, x0, **hyper), k, rounds, L, d * sn * sn, zeta2)
+    assert bad_lhs > bad_rhs, (bad_lhs, bad_rhs)
