@@ -21,7 +21,9 @@
  * representation of the averaged model); the representation of the local
  * model as averaged model minus gamma times the summed local gradients
  * (same proof); closed-form affine-map trajectory of the noiseless quadratic;
- * a hand-computed W=2, d=1 case; subset == full run.
+ * a hand-computed W=2, d=1 case; subset == full run; per-worker noise scale
+ * against the generator's own normals; the bound of Theorem 1 on workers that
+ * satisfy its assumptions (with a planted wrong-sign line 6 as negative control).
  */
 #include <math.h>
 #include <stddef.h>
