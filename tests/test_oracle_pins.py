@@ -438,3 +438,51 @@ def test_convergence_bound_of_theorem_1_holds_and_catches_a_wrong_correction():
             self.averaging = False
     bad_lhs, bad_rhs = _theorem1_sides(WrongSign(h, c, x0, **hyper), k, rounds, L, d * sn * sn, zeta2)
     assert bad_lhs > bad_rhs, (bad_lhs, bad_rhs)
+
+
+def test_mid_round_representation_of_the_local_model():
+    """Proof of Lemma 2: at ANY iteration t the local model is the averaged model of the last complete
+    communication, xhat at step (floor(t/k) - 1) k, minus gamma times the worker's own gradients since
+    that step -- a statement across two rounds (plain SGD)."""
+    W, n, k = 3, 25, 3
+    o = make(W, n, lr=0.1, noise_sigma=0.02, seed=4)
+    o.round(k)                                              # iterations 0 .. k-1
+    boundary_mean, since = None, []
+    for r in range(1, 4):                                   # rounds starting at t = r k
+        o.average_begin()
+        prev_mean, prev_grads = boundary_mean, since        # xhat_{(r-1)k} and the gradients of round r-1
+        boundary_mean, since = o.mean.copy(), []
+        for j in range(k):
+            if prev_mean is not None:                       # t = r k + j: floor(t/k) - 1 = r - 1
+                want = prev_mean[None, :] - o.lr * (np.sum(prev_grads, axis=0) + (np.sum(since, axis=0) if since else 0.0))
+                assert np.max(np.abs(o.x - want)) < 1e-13, (r, j)
+            since.append(o.local_steps(1, log_gradients=True)[0])
+        o.average_end_apply()
+
+
+def test_consensus_bound_of_lemma_2():
+    """Lemma 2 on the same kind of workers as the Theorem 1 pin: sum_i p_i sum_t ||xhat_t - x_t^i||^2 <=
+    8 gamma^2 k / (1 - 16 gamma^2 k^2 L^2) * (T N sigma^2 / sum M + 2 k T zeta^2 + 2 k sum_t ||grad f(xhat_t)||^2)."""
+    W, d, k, rounds = 4, 256, 3, 100
+    rng = np.random.default_rng(5)
+    h = np.tile(rng.uniform(0.5, 2.0, d).astype(np.float32), (W, 1))
+    c = rng.standard_normal((W, d)).astype(np.float32)
+    sn, gamma = 0.05, 0.02
+    L = float(h.max())
+    dev = h[0].astype(np.float64) * (c - c.mean(axis=0))
+    zeta2 = float(np.mean(np.sum(dev * dev, axis=1)))
+    o = orc.QuadraticOracle(h, c, rng.standard_normal(d), lr=gamma, noise_sigma=sn, seed=6)
+    gamma = o.lr
+    p = np.full(W, 1.0 / W)
+    lhs = grads = 0.0
+    for _ in range(rounds):
+        o.average_begin()
+        for _ in range(k):
+            lhs += o.consensus_distance()
+            g = o.objective(p @ o.x)[1]
+            grads += float(g @ g)
+            o.local_steps(1)
+        o.average_end_apply()
+    T = k * rounds
+    rhs = 8 * gamma**2 * k / (1 - 16 * gamma**2 * k**2 * L**2) * (T * d * sn * sn + 2 * k * T * zeta2 + 2 * k * grads)
+    assert 0 < lhs <= rhs and lhs > 0.01 * rhs, (lhs, rhs)
