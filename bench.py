@@ -135,6 +135,43 @@ def timelines(ctx, torch, P, k, rounds):
     return out
 
 
+def round_event_times(ctx, torch, stream, k, rounds, variant):
+    """Median and minimum round time from events recorded on the compute stream around every round
+    (every variant ends its round on that stream)."""
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 1)]
+    ctx.sync()
+    marks[0].record(stream)
+    for r in range(rounds):
+        ctx.average_begin()
+        if variant == "separate":
+            ctx.local_steps(k)
+            ctx.average_end_apply()
+        else:
+            ctx.local_steps_end_apply(k)
+        marks[r + 1].record(stream)
+    ctx.sync()
+    ms = sorted(marks[r].elapsed_time(marks[r + 1]) for r in range(rounds))
+    return {"round_ms_median": ms[len(ms) // 2], "round_ms_min": ms[0]}
+
+
+SINGLE_THREAD_SAMPLE = """
+import json, sys, time
+sys.path.insert(0, %r)
+import synth_inputs
+from oracle import cocod_oracle as orc
+cfg = synth_inputs.CONFIGS["C2_resnet18"]
+W, n, k = cfg["W"], cfg["d"] // 16, %d
+h, c = orc.fill_quadratic(cfg["seed"], W, n)
+o = orc.QuadraticOracle(h, c, lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"],
+                        noise_sigma=cfg["noise_sigma"], seed=cfg["seed"])
+o.round(k)
+t0 = time.perf_counter()
+for _ in range(3):
+    o.round(k)
+print(json.dumps({"per_round": (time.perf_counter() - t0) / 3, "threads": orc.num_threads(), "W": W, "n": n}))
+"""
+
+
 def cpu_baseline(cfg, k):
     """The oracle as it stands, timed on the host cores at the full workload shape for a few rounds."""
     from oracle import cocod_oracle as orc
@@ -150,9 +187,21 @@ def cpu_baseline(cfg, k):
     for _ in range(rounds):
         o.round(k)
     per_round = (time.perf_counter() - t0) / rounds
-    return {"value": W * d * k / per_round, "unit": "worker-param-updates/s", "cores": orc.num_threads(),
-            "kind": "oracle", "ms_per_round": per_round * 1e3,
-            "sample": "full shape W=%d d=%d k=%d, %d rounds after 1 untimed, fp64 C oracle with OpenMP" % (W, d, k, rounds)}
+    out = {"value": W * d * k / per_round, "unit": "worker-param-updates/s", "cores": orc.num_threads(),
+           "kind": "oracle", "ms_per_round": per_round * 1e3,
+           "model_GBps": model_round_bytes(W, d, k) / per_round / 1e9,     # the round's fp32 byte model, for comparison only
+           "sample": "full shape W=%d d=%d k=%d, %d rounds after 1 untimed, fp64 C oracle with OpenMP" % (W, d, k, rounds)}
+    # the same oracle on ONE thread (child process with OMP_NUM_THREADS=1), on the first d/16 columns
+    import subprocess
+    try:
+        r = subprocess.run([sys.executable, "-c", SINGLE_THREAD_SAMPLE % (ROOT, k)], capture_output=True, text=True,
+                           timeout=240, env=dict(os.environ, OMP_NUM_THREADS="1"))
+        one = json.loads(r.stdout.strip().splitlines()[-1])
+        out["single_thread"] = {"value": one["W"] * one["n"] * k / one["per_round"], "threads": one["threads"],
+                                "sample": "W=%d, first %d columns, k=%d, 3 rounds after 1 untimed" % (one["W"], one["n"], k)}
+    except Exception as e:                  # the baseline is a report, never a reason to fail the benchmark
+        out["single_thread"] = {"value": None, "error": str(e)[:200]}
+    return out
 
 
 def roofline(name, algorithmic_bytes, seconds, launches, traffic):
@@ -273,6 +322,15 @@ def main():
                     momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], noise_sigma=cfg["noise_sigma"],
                     seed=cfg["seed"], tensor_numel=sizes, bucket_bytes=cfg.get("bucket_bytes", 0),
                     compute_stream=s_compute, avg_stream=s_avg)
+    # what a plain copy of one [W][stride] array reaches on this machine, same launch path (h -> c, before they are filled)
+    for timed in (False, True):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20 if timed else 3):
+            P.debug_copy(s_compute, h, c, W * stride)
+        ctx.sync()
+        copy_s = (time.perf_counter() - t0) / 20
+    copy_gbps = 8.0 * W * stride / copy_s / 1e9
     ctx.fill_quadratic()
     ctx.sync()
 
@@ -297,7 +355,10 @@ def main():
         "round_model_GBps": model_round_bytes(W, d, k) / per_round / 1e9,
         "round_moved_GBps": moved_round_bytes(W, d, k, variant) / per_round / 1e9,
         "round_moved_frac_of_hbm_peak": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / HBM_PEAK_GBS,
+        "copy_kernel_GBps": copy_gbps,          # plain copy of a [W][stride] array on this machine, read + write
+        "round_moved_frac_of_copy_kernel": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / copy_gbps,
     }
+    out.update(round_event_times(ctx, torch, s_compute, k, args.steps, variant))
     # "roofline" is the kernel with the largest share of the round's GPU time: with line 6 inside the
     # last step that is this last step (it moves more bytes than a plain step); the plain step rides
     # along as "roofline_plain_step" (at k = 2 it always shares the memory system with the mean).
