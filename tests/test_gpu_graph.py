@@ -9,8 +9,7 @@ import paper_1906_12043_amd as P
 import synth_inputs
 from oracle import cocod_oracle as orc
 from oracle import mlp_oracle
-from gpu_harness import GpuWorkers, rel_err
-from test_gpu_mlp import GpuMlp
+from tests.gpu_harness import GpuMlp, GpuWorkers, rel_err
 
 pytestmark = pytest.mark.gpu
 

@@ -8,60 +8,10 @@ import torch
 import paper_1906_12043_amd as P
 import synth_inputs
 from oracle import mlp_oracle as mlp
-from tests.gpu_harness import rel_err
+from tests.gpu_harness import GpuMlp, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
-
-
-class GpuMlp:
-    def __init__(self, W, shape, batch, theta0, **hyper):
-        n_in, n_hidden, n_out = shape
-        self.W, self.shape, self.batch = W, shape, batch
-        self.d = synth_inputs.mlp_param_count(*shape)
-        self.dev = torch.device("cuda:0")
-        self.stride, _, _ = P.plan_layout(self.d)
-        self.xA = torch.zeros((W, self.stride), device=self.dev)
-        self.xA[:, :self.d] = torch.from_numpy(np.asarray(theta0, dtype=np.float32)).to(self.dev)
-        self.xB = torch.full((W, self.stride), float("nan"), device=self.dev)
-        self.v = torch.zeros((W, self.stride), device=self.dev)
-        self.mean = torch.zeros(self.stride, device=self.dev)
-        self.s_compute, self.s_avg = torch.cuda.Stream(device=self.dev), torch.cuda.Stream(device=self.dev)
-        torch.cuda.synchronize()
-        self.ctx = P.Context(W=W, d=self.d, stride=self.stride, xA=self.xA, xB=self.xB, v=self.v, mean=self.mean,
-                             grad=P.GRAD_MLP, mlp=(n_in, n_hidden, n_out, batch),
-                             compute_stream=self.s_compute, avg_stream=self.s_avg, **hyper)
-
-    def x(self):
-        self.ctx.sync()
-        live = self.xA if self.ctx.live_model() == self.xA.data_ptr() else self.xB
-        return live[:, :self.d].cpu().numpy().astype(np.float64)
-
-    def vel(self):
-        self.ctx.sync()
-        return self.v[:, :self.d].cpu().numpy().astype(np.float64)
-
-    def workspace(self):
-        """Copies of X, H, dA, dZ, y as numpy arrays (through the library's own copy kernel)."""
-        self.ctx.sync()
-        ptrs, pitch = self.ctx.mlp_workspace()
-        n_in, n_hidden, n_out = self.shape
-        sizes = dict(X=self.batch * n_in, H=self.batch * n_hidden, dA=self.batch * n_hidden, dZ=self.batch * pitch, y=self.batch)
-        out = {}
-        for name, per_worker in sizes.items():
-            buf = torch.empty(self.W * per_worker, device=self.dev)
-            P.debug_copy(None, ptrs[name], buf, buf.numel())
-            torch.cuda.synchronize()
-            out[name] = buf.view(torch.int32).cpu().numpy() if name == "y" else buf.cpu().numpy().astype(np.float64)
-        out["X"] = out["X"].reshape(self.W, self.batch, n_in)
-        out["H"] = out["H"].reshape(self.W, self.batch, n_hidden)
-        out["dA"] = out["dA"].reshape(self.W, self.batch, n_hidden)
-        out["dZ"] = out["dZ"].reshape(self.W, self.batch, pitch)[:, :, :n_out]
-        out["y"] = out["y"].reshape(self.W, self.batch)
-        return out
-
-    def close(self):
-        self.ctx.close()
 
 
 HYPER = dict(lr=0.05, momentum=0.9, weight_decay=1e-3, seed=0x5EED0004)
