@@ -135,6 +135,36 @@ def timelines(ctx, torch, P, k, rounds):
     return out
 
 
+def external_gradient_rounds(ctx, torch, W, d, stride, k, rounds, g32, scratch):
+    """The round with the caller's gradient (a real model's backward pass would write it): k steps of
+    cocod_external_step, the last one closing the round with line 6 inside, for fp32 gradients (20 B per
+    worker-parameter and step) and 16-bit ones (18 B).  The gradient buffers are whatever the workload's
+    h array holds (fp32) and a 16-bit view of its c array: the arithmetic does not matter here, the bytes do."""
+    g16 = scratch.view(torch.bfloat16).reshape(-1)[:W * stride].view(W, stride)   # a dense [W][stride] block of 16-bit elements
+    out = {}
+    for name, call, g, gbytes in (("fp32", ctx.external_step, g32, 4), ("bf16", ctx.external_step_bf16, g16, 2)):
+        def one_round():
+            ctx.average_begin()
+            for s in range(k):
+                call(g, close_round=(s == k - 1))
+        for _ in range(2):
+            one_round()
+        ctx.sync()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            one_round()
+        ctx.sync()
+        per_round = (time.perf_counter() - t0) / rounds
+        step_bytes = STEP_BYTES - 8 + gbytes                  # r x, v, g; w x, v
+        # + the mean's pass, + the mean read by the last step, + the stored model there (at k = 1 the step reads it anyway)
+        moved = W * d * (step_bytes * k + 4 * (1 + 1 / W) + 4 / W + (4 if k > 1 else 0))
+        out[name] = {"ms_per_round": per_round * 1e3, "updates_per_s": W * d * k / per_round,
+                     "moved_GBps": moved / per_round / 1e9, "bytes_per_worker_param_step": step_bytes}
+    out["k"] = k
+    return out
+
+
 def round_event_times(ctx, torch, stream, k, rounds, variant):
     """Median and minimum round time from events recorded on the compute stream around every round
     (every variant ends its round on that stream)."""
@@ -399,6 +429,7 @@ def main():
             sched[name] = pr * 1e3
         out["separate_schedule_ms_per_round"] = sched
         out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, args.steps)
+        out["external_gradient"] = external_gradient_rounds(ctx, torch, W, d, stride, k, args.steps, h, c)
     ctx.close()
     del xA, xB, v, mean, h, c
     torch.cuda.empty_cache()
