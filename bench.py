@@ -389,6 +389,9 @@ def main():
         "round_moved_frac_of_copy_kernel": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / copy_gbps,
     }
     out.update(round_event_times(ctx, torch, s_compute, k, args.steps, variant))
+    prop = torch.cuda.get_device_properties(0)
+    out["device"] = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
+                     "hbm_GiB": prop.total_memory / 2**30, "hip": torch.version.hip}
     # "roofline" is the kernel with the largest share of the round's GPU time: with line 6 inside the
     # last step that is this last step (it moves more bytes than a plain step); the plain step rides
     # along as "roofline_plain_step" (at k = 2 it always shares the memory system with the mean).
