@@ -12,6 +12,7 @@
 // For line 6 the same thread serves all W workers of its column, so the mean is
 // read once per column instead of once per worker (12 + 4/W bytes per parameter).
 #include "internal.hpp"
+#include "mean_sum.hpp"
 
 namespace cocod {
 namespace {
@@ -37,28 +38,23 @@ __device__ __forceinline__ void st4_stream(float *p, const float4 &a)
 template <bool WEIGHTED>
 __device__ __forceinline__ float4 column_mean(const float *col, uint64_t stride, uint32_t W, const float *weights)
 {
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    MeanSum acc;
+    acc.clear();
     uint32_t i = 0;
     for (; i + kRowBatch <= W; i += kRowBatch) {
         float4 r[kRowBatch];
         #pragma unroll
         for (int b = 0; b < kRowBatch; ++b) r[b] = ld4_stream(col + static_cast<uint64_t>(i + b) * stride);
         #pragma unroll
-        for (int b = 0; b < kRowBatch; ++b) {
-            const float pw = WEIGHTED ? weights[i + b] : 1.0f;
-            acc.x += pw * r[b].x; acc.y += pw * r[b].y; acc.z += pw * r[b].z; acc.w += pw * r[b].w;
-        }
+        for (int b = 0; b < kRowBatch; ++b)
+            acc.add<WEIGHTED>(WEIGHTED ? weights[i + b] : 1.0f, r[b].x, r[b].y, r[b].z, r[b].w);
     }
     for (; i < W; ++i) {
         const float4 r = ld4_stream(col + static_cast<uint64_t>(i) * stride);
-        const float pw = WEIGHTED ? weights[i] : 1.0f;
-        acc.x += pw * r.x; acc.y += pw * r.y; acc.z += pw * r.z; acc.w += pw * r.w;
+        acc.add<WEIGHTED>(WEIGHTED ? weights[i] : 1.0f, r.x, r.y, r.z, r.w);
     }
-    if (!WEIGHTED) {
-        const float inv = 1.0f / static_cast<float>(W);
-        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-    }
-    return acc;
+    acc.finish<WEIGHTED>(W);
+    return make_float4(acc.s[0], acc.s[1], acc.s[2], acc.s[3]);
 }
 
 template <bool WEIGHTED>
@@ -133,18 +129,15 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
     #pragma unroll
     for (int i = 0; i < R; ++i)
         if (static_cast<uint32_t>(i) < W) s[i] = ld4_stream(snap + e + static_cast<uint64_t>(i) * stride);
-    float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+    MeanSum acc;
+    acc.clear();
     #pragma unroll
     for (int i = 0; i < R; ++i) {                          // same order and operations as column_mean
-        if (static_cast<uint32_t>(i) < W) {                // guard, not break: the loop must unroll fully or s[] goes to scratch
-            const float pw = WEIGHTED ? weights[i] : 1.0f;
-            m.x += pw * s[i].x; m.y += pw * s[i].y; m.z += pw * s[i].z; m.w += pw * s[i].w;
-        }
+        if (static_cast<uint32_t>(i) < W)                  // guard, not break: the loop must unroll fully or s[] goes to scratch
+            acc.add<WEIGHTED>(WEIGHTED ? weights[i] : 1.0f, s[i].x, s[i].y, s[i].z, s[i].w);
     }
-    if (!WEIGHTED) {
-        const float inv = 1.0f / static_cast<float>(W);
-        m.x *= inv; m.y *= inv; m.z *= inv; m.w *= inv;
-    }
+    acc.finish<WEIGHTED>(W);
+    const float4 m = make_float4(acc.s[0], acc.s[1], acc.s[2], acc.s[3]);
     st4(mean + e, m);
     #pragma unroll
     for (int i = 0; i < R; ++i) {
@@ -164,6 +157,20 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
 // belong: per thread a column quad (two passes over the W rows, the second one from cache), then a
 // butterfly over the wave, the four wave sums through LDS, one double per block; a second one-block
 // kernel adds the block partials in a fixed order, so the result is deterministic.
+// the same mean with ordinary (cached) loads: the diagnostics read the models twice
+template <bool WEIGHTED>
+__device__ __forceinline__ float4 column_mean_cached(const float *col, uint64_t stride, uint32_t W, const float *weights)
+{
+    MeanSum acc;
+    acc.clear();
+    for (uint32_t i = 0; i < W; ++i) {
+        const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
+        acc.add<WEIGHTED>(WEIGHTED ? weights[i] : 1.0f, r.x, r.y, r.z, r.w);
+    }
+    acc.finish<WEIGHTED>(W);
+    return make_float4(acc.s[0], acc.s[1], acc.s[2], acc.s[3]);
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
     #pragma unroll
@@ -182,12 +189,7 @@ __global__ __launch_bounds__(kStepThreads) void consensus_partial_kernel(const C
     if (e < ck.n) {
         const float *col = x + static_cast<uint64_t>(ck.mem_quad) * 4 + e;
         const float uniform = 1.0f / static_cast<float>(W);
-        float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (uint32_t i = 0; i < W; ++i) {
-            const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
-            const float pw = WEIGHTED ? weights[i] : uniform;
-            m.x += pw * r.x; m.y += pw * r.y; m.z += pw * r.z; m.w += pw * r.w;
-        }
+        const float4 m = column_mean_cached<WEIGHTED>(col, stride, W, weights);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (uint32_t i = 0; i < W; ++i) {
             const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
@@ -241,12 +243,7 @@ __global__ __launch_bounds__(kStepThreads) void objective_partial_kernel(const C
     if (e < ck.n) {
         const uint64_t at = static_cast<uint64_t>(ck.mem_quad) * 4 + e;
         const float uniform = 1.0f / static_cast<float>(W);
-        float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (uint32_t i = 0; i < W; ++i) {
-            const float4 r = ld4(x + at + static_cast<uint64_t>(i) * stride);
-            const float pw = WEIGHTED ? weights[i] : uniform;
-            m.x += pw * r.x; m.y += pw * r.y; m.z += pw * r.z; m.w += pw * r.w;
-        }
+        const float4 m = column_mean_cached<WEIGHTED>(x + at, stride, W, weights);
         float4 f = make_float4(0.f, 0.f, 0.f, 0.f), g = make_float4(0.f, 0.f, 0.f, 0.f);
         for (uint32_t i = 0; i < W; ++i) {
             const float4 hr = ld4(h + at + static_cast<uint64_t>(i) * stride);

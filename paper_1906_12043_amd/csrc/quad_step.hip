@@ -24,6 +24,7 @@
 // cross-lane moves (one LDS word across a wave boundary) instead of a second generator call.
 #include "internal.hpp"
 #include "philox.hpp"
+#include "mean_sum.hpp"
 
 #include <hip/hip_ext.h>
 
@@ -187,7 +188,8 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_head_kernel(const Step
         return r;
     };
 
-    f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+    MeanSum acc;
+    acc.clear();
     Row ring[DEPTH];
     #pragma unroll
     for (int j = 0; j < DEPTH; ++j) ring[j] = load_row(static_cast<uint32_t>(j) < p.W ? j : 0);
@@ -198,8 +200,7 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_head_kernel(const Step
         if (w >= p.W) break;
         const Row cur = ring[j];
         if (w + DEPTH < p.W) ring[j] = load_row(w + DEPTH);
-        const float pw = WEIGHTED ? p.weights[w] : 1.0f;
-        acc.x += pw * cur.x.x; acc.y += pw * cur.x.y; acc.z += pw * cur.x.z; acc.w += pw * cur.x.w;
+        acc.add<WEIGHTED>(WEIGHTED ? p.weights[w] : 1.0f, cur.x.x, cur.x.y, cur.x.z, cur.x.w);
 
         f4 g = cur.h * (cur.x - cur.c);
         if (GRAD == kGradQuadNoisy)
@@ -219,12 +220,10 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_head_kernel(const Step
         if (HAS_V) store_quad(make_rsrc(p.v + row, bytes), off, v);
       }
     }
-    if (!WEIGHTED) {
-        const float inv = 1.0f / static_cast<float>(p.W);
-        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-    }
+    acc.finish<WEIGHTED>(p.W);
     // the mean is read again by line 6: ordinary (cached) store
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, acc), make_rsrc(p.mean_out + col, bytes),
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, f4{acc.s[0], acc.s[1], acc.s[2], acc.s[3]}),
+                                           make_rsrc(p.mean_out + col, bytes),
                                            static_cast<int>(off), 0, 0);
 }
 

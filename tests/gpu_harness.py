@@ -43,8 +43,10 @@ class GpuWorkers:
             self.c = torch.empty((W, self.stride), device=self.dev)
         else:
             self.h, self.c = self._upload(h), self._upload(c)
-        self.s_compute = torch.cuda.Stream(device=self.dev)
-        self.s_avg = torch.cuda.Stream(device=self.dev) if two_streams else self.s_compute
+        # two_streams: True = compute and averaging streams of their own; False = one stream for both;
+        # "null" = the null stream for both (no stream objects at all)
+        self.s_compute = None if two_streams == "null" else torch.cuda.Stream(device=self.dev)
+        self.s_avg = torch.cuda.Stream(device=self.dev) if two_streams is True else self.s_compute
         torch.cuda.synchronize()
         self.ctx = P.Context(W=W, d=d, stride=self.stride, xA=self.xA, xB=self.xB, v=self.v, mean=self.mean,
                              h=self.h, c=self.c, tensor_numel=tensor_numel, bucket_bytes=bucket_bytes,

@@ -75,7 +75,7 @@ def test_tiny_config_every_round():
     (1, 1, 0.0, 0.0, 0.01, 2), (1, 5, 0.9, 5e-4, 0.01, 3), (3, 3, 0.9, 0.0, 0.0, 1), (2, 4, 0.5, 0.01, 0.1, 4),
     (4, 4097, 0.9, 5e-4, 0.01, 2), (16, 10007, 0.9, 5e-4, 0.01, 2), (5, 12289, 0.0, 0.0, 0.01, 3),
     (64, 4100, 0.9, 5e-4, 0.01, 1), (7, 8192, 0.9, 0.0, 0.0, 8),
-    (1000, 5, 0.9, 5e-4, 0.01, 2), (3, 1023, 0.9, 5e-4, 0.01, 2), (3, 1025, 0.0, 5e-4, 0.01, 2), (17, 2047, 0.9, 0.0, 0.01, 3),
+    (65535, 3, 0.9, 5e-4, 0.01, 2), (1000, 5, 0.9, 5e-4, 0.01, 2), (3, 1023, 0.9, 5e-4, 0.01, 2), (3, 1025, 0.0, 5e-4, 0.01, 2), (17, 2047, 0.9, 0.0, 0.01, 3),
 ])
 def test_small_shapes_ragged_tails(W, d, mu, wd, sigma, k):
     hyper = dict(lr=0.05, momentum=mu, weight_decay=wd, noise_sigma=sigma, seed=1000 + d)
@@ -178,7 +178,7 @@ def test_overlapped_round_is_bit_identical_to_serialised_rounds():
     W, d, rounds, k = 8, 300_001, 6, 2
     ref = run_bits(W, d, rounds, k, P.SCHED_OVERLAP, two_streams=False)
     for schedule, two in [(P.SCHED_OVERLAP, True), (P.SCHED_SERIAL, True), (P.SCHED_FUSED, True), (P.SCHED_FUSED, False),
-                          (P.SCHED_HEAD, True), (P.SCHED_HEAD, False)]:
+                          (P.SCHED_HEAD, True), (P.SCHED_HEAD, False), (P.SCHED_OVERLAP, "null"), (P.SCHED_FUSED, "null")]:
         got = run_bits(W, d, rounds, k, schedule, two_streams=two)
         assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]), (schedule, two)
 
