@@ -108,6 +108,30 @@ def test_steps_outside_a_round_and_zero_step_round():
     g.close()
 
 
+@pytest.mark.parametrize("graph", [False, True])
+def test_step_counter_at_the_top_of_its_range(graph):
+    """t is a 32-bit word of the generator's counter: the last representable steps must key the noise
+    as the oracle does, also when a graph replay reads t from its device word."""
+    W, d, k = 3, 4100, 3
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=0xFFFFFFFF12345678)
+    h, c = synth_inputs.quadratic_data(41, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, **hyper)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    for start in (2**31 - 2, 2**32 - 1 - 2 * k):
+        g.ctx.set_step(start); o.step = start
+        for _ in range(2):
+            if graph:
+                g.ctx.graph_round(k, True)
+            else:
+                g.ctx.round(k)
+            o.round(k)
+            check_state(g, o, what="t = %d" % o.step)
+        assert g.ctx.get_step() == o.step
+    with pytest.raises(P.CocodError):
+        g.ctx.local_steps(1)                      # the counter itself must stay below 2^32
+    g.close()
+
+
 def test_single_worker_first_round_is_exactly_plain_sgd():
     """N = 1 from x0 = 0: snapshot and mean are 0, so line 6 returns the local model bit for bit."""
     d = 9000
