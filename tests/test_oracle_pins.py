@@ -85,7 +85,7 @@ def test_single_worker_with_nonzero_start_and_split_calls():
     assert np.array_equal(a.x, b.x) and np.array_equal(a.v, b.v) and a.step == b.step == 4
 
 
-@pytest.mark.parametrize("W", [4, 16])
+@pytest.mark.parametrize("W", [4, 16, 64])
 def test_identical_workers_without_noise_follow_one_worker(W):
     n, R, k = 100, 5, 2
     h1, c1 = synth_inputs.quadratic_data(8, 1, n)
