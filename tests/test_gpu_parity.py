@@ -145,6 +145,26 @@ def test_single_worker_first_round_is_exactly_plain_sgd():
     a.close(); b.close()
 
 
+@pytest.mark.parametrize("W", [4, 16, 64])
+def test_identical_workers_without_noise_follow_one_worker_bit_for_bit(W):
+    """Same h, c on every worker and no noise: the mean of W equal values is exact for a power of two,
+    so every worker retraces the single-worker rounds bit for bit."""
+    d, k = 5001, 2
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.0, seed=1)
+    h1, c1 = synth_inputs.quadratic_data(33, 1, d)
+    one = GpuWorkers(1, d, h=h1, c=c1, **hyper)
+    many = GpuWorkers(W, d, h=np.repeat(h1, W, 0), c=np.repeat(c1, W, 0), **hyper)
+    o = orc.QuadraticOracle(h1, c1, **hyper)
+    for r in range(4):
+        for g in (one, many):
+            g.ctx.round(k) if r % 2 else g.ctx.round_fused_tail(k)
+        o.round(k)
+    x1, xm = one.x_raw()[:, :d], many.x_raw()[:, :d]
+    assert all(torch.equal(xm[i], x1[0]) for i in range(W))
+    check_state(one, o, what="single worker")
+    one.close(); many.close()
+
+
 def test_weighted_mean():
     W, d, k = 4, 6001, 2
     p = [0.125, 0.25, 0.25, 0.375]
