@@ -165,6 +165,30 @@ def test_identical_workers_without_noise_follow_one_worker_bit_for_bit(W):
     one.close(); many.close()
 
 
+@pytest.mark.parametrize("weights", [None, [0.4, 0.3, 0.2, 0.1]])
+def test_line6_invariants_on_device_data(weights):
+    """The two representations in the proof of Lemma 2, checked on what the device itself holds (no
+    oracle): after line 6 the weighted mean of the models is the old mean plus the weighted mean of the
+    local progress, and each worker's deviation from it is its own progress minus the mean progress."""
+    W, d, k = 4, 20_003, 3
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=19, weights=weights)
+    h, c = synth_inputs.quadratic_data(23, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, **hyper)
+    p = np.full(W, 1.0 / W) if weights is None else np.asarray(weights, dtype=np.float64)
+    g.ctx.round(k); g.ctx.round(k)                              # a state where the workers differ
+    snap = g.x()
+    g.ctx.average_begin(); g.ctx.local_steps(k)
+    pre = g.x()
+    g.ctx.average_end_apply()
+    post, mean = g.x(), g.avg()
+    delta = pre - snap
+    tol = 4e-7 * (1 + np.abs(post).max())
+    assert np.max(np.abs(mean - p @ snap)) <= tol
+    assert np.max(np.abs(p @ post - (mean + p @ delta))) <= tol
+    assert np.max(np.abs((post - p @ post) - (delta - p @ delta))) <= tol
+    g.close()
+
+
 def test_weighted_mean():
     W, d, k = 4, 6001, 2
     p = [0.125, 0.25, 0.25, 0.375]
