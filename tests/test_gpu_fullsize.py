@@ -82,8 +82,14 @@ def test_resnet18_size_full_vector_three_rounds():
         g.ctx.round(k); o.round(k)
     ex, ev = rel_err(g.x(), o.x), rel_err(g.vel(), o.v)
     print("C2 full vector, 3 rounds k=2: rel err x %.3g v %.3g" % (ex, ev))
+    # the reduction diagnostics over all 179 M worker-parameters against the oracle's full-vector values
+    cons, want_cons = g.ctx.consensus_distance(), o.consensus_distance()
+    (f, g2), (want_f, want_g2) = g.ctx.quadratic_objective(), o.objective_at_mean()
+    print("  consensus distance %.6g (oracle %.6g), f(mean) %.6g (%.6g), |grad f(mean)|^2 %.6g (%.6g)"
+          % (cons, want_cons, f, want_f, g2, want_g2))
     g.close()
     assert ex <= TOL and ev <= 10 * TOL
+    assert abs(cons - want_cons) <= 1e-5 * want_cons and abs(f - want_f) <= 1e-5 * want_f and abs(g2 - want_g2) <= 1e-5 * want_g2
 
 
 @pytest.mark.parametrize("k", [1, 2, 4])
