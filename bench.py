@@ -431,6 +431,14 @@ def main():
             pr = time_rounds(ctx, torch, k, args.steps, 2, "separate", False)[0]
             sched[name] = pr * 1e3
         out["separate_schedule_ms_per_round"] = sched
+        # line 6 inside the last step, with the mean (a) beside the first k-1 steps on its own stream,
+        # (b) on the compute stream right before the last step, (c) inside the first step
+        sched = {}
+        for name, code in (("overlap", P.SCHED_OVERLAP), ("serial", P.SCHED_SERIAL), ("head", P.SCHED_HEAD)):
+            ctx.set_schedule(code)
+            sched[name] = time_rounds(ctx, torch, k, args.steps, 2, "fused_tail", False)[0] * 1e3
+        ctx.set_schedule(P.SCHED_OVERLAP)
+        out["fused_tail_schedule_ms_per_round"] = sched
         out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, args.steps)
         out["external_gradient"] = external_gradient_rounds(ctx, torch, W, d, stride, k, args.steps, h, c)
     ctx.close()
