@@ -297,3 +297,20 @@ def test_launch_size_limits():
         assert ctx.get_plan() == (2**30, 2**20, 1)
         ctx.round(2)
         ctx.round_fused_tail(1)
+
+
+def test_plain_c_client_of_the_abi(tmp_path):
+    """The header is C (compiled -std=c99 -pedantic, warnings are errors) and the library is usable from a
+    C program with no Python in between: tests/c_abi_client.c walks a dry-run context."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "c_abi_client")
+    libdir = os.path.dirname(P.lib_path())
+    build = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                            os.path.join(ROOT, "tests", "c_abi_client.c"), "-o", exe, "-L", libdir, "-lcocod",
+                            "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0 and "c abi client: ok" in run.stdout, run.stderr
