@@ -77,6 +77,33 @@ def test_graph_rounds_match_eager_rounds_bit_for_bit(packed, two_streams, fused_
     e.close(); g.close()
 
 
+def test_contexts_release_what_they_own():
+    """Create, use (graph rounds, diagnostics, every schedule) and destroy many contexts: the device memory
+    the library allocated for itself (tables, scratch, step word, graphs) must come back."""
+    W, d = 4, 50_000
+    h, c = synth_inputs.quadratic_data(2, W, d)
+    keep = GpuWorkers(W, d, h=h, c=c, **HYPER)              # the caller's buffers, reused by every context below
+    def cycle():
+        ctx = P.Context(W=W, d=d, stride=keep.stride, xA=keep.xA, xB=keep.xB, v=keep.v, mean=keep.mean, h=keep.h, c=keep.c,
+                        compute_stream=keep.s_compute, avg_stream=keep.s_avg, weights=[0.25] * W,
+                        noise_sigma_w=[0.01] * W, **HYPER)
+        for sched in (P.SCHED_OVERLAP, P.SCHED_HEAD):
+            ctx.set_schedule(sched)
+            ctx.graph_round(2, True); ctx.graph_round(2, True); ctx.graph_round(1, False)
+        ctx.consensus_distance(); ctx.quadratic_objective()
+        ctx.close()
+    keep.ctx.close()
+    for _ in range(3):
+        cycle()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(40):
+        cycle()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < (8 << 20), (free0, free1)
+
+
 def test_graph_rounds_of_mlp_workers_match_eager_rounds_and_oracle():
     W, shape, batch, k, rounds = 3, (128, 64, 10), 128, 2, 5
     theta0 = synth_inputs.mlp_he_init(11, *shape)
