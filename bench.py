@@ -388,6 +388,11 @@ def main():
         "copy_kernel_GBps": copy_gbps,          # plain copy of a [W][stride] array on this machine, read + write
         "round_moved_frac_of_copy_kernel": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / copy_gbps,
     }
+    if args.workload == "C2" and variant == "fused_tail" and k >= 1:
+        # the same round by the hardware counters (bytes across the L2 boundary per launch, from the counter
+        # runs under profiles/): k-1 plain steps, the mean (4(1+1/W) B, ratio 1.000), the step with line 6
+        counted = (k - 1) * STEP_TRAFFIC_BYTES + 4 * (1 + 1 / W) * W * d + TAIL_TRAFFIC_BYTES[min(k, 2)]
+        out["round_counter_GBps"] = counted / per_round / 1e9
     out.update(round_event_times(ctx, torch, s_compute, k, args.steps, variant))
     prop = torch.cuda.get_device_properties(0)
     out["device"] = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
