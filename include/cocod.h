@@ -134,7 +134,7 @@ typedef struct cocod_config {
  *   bucket_begin  out, may be NULL: [n_tensors + 1] capacity; bucket b covers elements
  *                 [bucket_begin[b], bucket_begin[b+1]) of a worker; n_buckets + 1 entries written.
  * Follows the packed-buffer practice of the communication library the paper used
- * (tensor fusion); the paper itself only needs "the model" as one vector.
+ * (tensor fusion); Algorithm 1 itself treats the model as one vector.
  */
 int cocod_plan_layout(uint64_t d, uint32_t n_tensors, const uint64_t *tensor_numel,
                       uint64_t bucket_bytes, uint64_t *padded_d, uint64_t *tensor_offset,

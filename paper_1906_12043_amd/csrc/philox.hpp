@@ -2,9 +2,9 @@
 //
 // Generator: Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).
 // Keying: key = (seed low, seed high); counter = (j >> 2, step, worker, tag), so
-// one 128-bit block serves the four consecutive parameters 4q .. 4q+3.  The
-// paper's Step II only asks for "a mini-batch stochastic gradient"; the seeded
-// noise stands in for the sampling of the mini-batch.
+// one 128-bit block serves the four consecutive parameters 4q .. 4q+3.  Step II
+// of Algorithm 1 only requires some stochastic gradient of a mini-batch; the
+// seeded noise stands in for the sampling of that mini-batch.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
