@@ -40,7 +40,11 @@ def subset_parity(cfg, k, n_random=100_000, tensor_numel=None, bucket_bytes=0, s
     starts = list(np.cumsum([0] + list(tensor_numel))[:-1]) if tensor_numel else []
     cols = synth_inputs.sample_columns(cfg["seed"] + k, d, n_random, edge_columns(d, starts))
     ii = cols.astype(np.int64)
-    g = GpuWorkers(W, d, device_fill=True, tensor_numel=tensor_numel, bucket_bytes=bucket_bytes, **hyper_of(cfg))
+    # the launch configuration the benchmark times: worker rows on 4 KiB boundaries, data drawn on the device
+    padded = P.plan_layout(d, tensor_numel, bucket_bytes)[0]
+    g = GpuWorkers(W, d, device_fill=True, tensor_numel=tensor_numel, bucket_bytes=bucket_bytes,
+                   extra_stride=-padded % 1024, **hyper_of(cfg))
+    assert g.stride % 1024 == 0
     h, c = orc.fill_quadratic(cfg["seed"], W, idx=cols)
     hg, cg = g.data(ii)
     assert np.array_equal(hg, h) and np.max(np.abs(cg.astype(np.float64) - c)) < 2e-6
