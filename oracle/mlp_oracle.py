@@ -16,7 +16,12 @@ Readings (the paper only says "mini-batch stochastic gradient"; the workload is 
   * optimizer and line 6 as in the quadratic oracle: g = G + wd x; v = mu v + g; x = x - lr v;
     momentum buffers stay local.
 Pins: tests/test_oracle_mlp.py (finite differences, an autograd library on the same net, softmax
-and gradient-sum identities, W = 1 reduces to plain SGD, mean preservation by line 6).
+and gradient-sum identities, the optimizer lines against a library optimizer and against hand values,
+W = 1 reduces to plain SGD, mean preservation by line 6).
+
+Diagnostic mirrors (never the reference): `state_dtype=np.float32` rounds x and v to fp32 after every
+update while all arithmetic stays fp64; `compute_dtype=np.float32` runs every operation in fp32.
+They measure how far ANY fp32 evaluation of this iteration drifts from the fp64 one.
 """
 import numpy as np
 
@@ -72,19 +77,21 @@ class MlpOracle:
     """W workers, each a copy of the perceptron; methods are the steps of Algorithm 1."""
 
     def __init__(self, theta0, W, n_in, n_hidden, n_out, batch, *, lr, momentum=0.0, weight_decay=0.0,
-                 seed=0, weights=None):
+                 seed=0, weights=None, state_dtype=None, compute_dtype=np.float64):
         self.W, self.shape, self.batch = W, (n_in, n_hidden, n_out), batch
-        theta0 = np.asarray(theta0, dtype=np.float64)
+        self.real = np.dtype(compute_dtype).type   # np.float64: the oracle; np.float32: diagnostic mirror
+        self.state_dtype = state_dtype             # diagnostic mirror: state rounded to this type after every update
+        theta0 = np.asarray(theta0, dtype=self.real)
         self.d = theta0.shape[-1]
         assert self.d == n_in * n_hidden + n_hidden + n_hidden * n_out + n_out
-        self.x = np.empty((W, self.d))
+        self.x = np.empty((W, self.d), dtype=self.real)
         self.x[...] = theta0                       # every worker starts from the same point
         self.v = np.zeros_like(self.x)
         self.snap = np.zeros_like(self.x)
-        self.mean = np.zeros(self.d)
-        self.lr, self.mu, self.wd = orc.f32(lr), orc.f32(momentum), orc.f32(weight_decay)
+        self.mean = np.zeros(self.d, dtype=self.real)
+        self.lr, self.mu, self.wd = (self.real(orc.f32(a)) for a in (lr, momentum, weight_decay))
         self.seed = int(seed)
-        self.p = np.full(W, 1.0 / W) if weights is None else np.asarray(weights, dtype=np.float64)
+        self.p = (np.full(W, 1.0 / W) if weights is None else np.asarray(weights, dtype=np.float64)).astype(self.real)
         self.step = 0
         self.averaging = False
         self.last_loss = np.zeros(W)
@@ -97,12 +104,16 @@ class MlpOracle:
         for _ in range(k):
             for i in range(self.W):
                 X, y = minibatch(self.seed, i, self.step, self.batch, n_in, n_out)
-                self.last_loss[i], G, amb = loss_and_gradient(self.x[i], X, y, n_in, n_hidden, n_out, self.margin)
+                self.last_loss[i], G, amb = loss_and_gradient(self.x[i], X.astype(self.real), y, n_in, n_hidden, n_out,
+                                                              self.margin)
                 self.ambiguous[i].update(int(n) for n in amb)
                 g = G + self.wd * self.x[i]
-                self.v[i] = self.mu * self.v[i] + g
-                self.x[i] = self.x[i] - self.lr * self.v[i]
+                self.v[i] = self._stored(self.mu * self.v[i] + g)
+                self.x[i] = self._stored(self.x[i] - self.lr * self.v[i])
             self.step += 1
+
+    def _stored(self, a):
+        return a if self.state_dtype is None else a.astype(self.state_dtype).astype(self.real)
 
     def certain_mask(self):
         """[W][d] bool: False on the parameters (column n of W1, b1[n]) fed by a borderline relu unit
@@ -126,7 +137,7 @@ class MlpOracle:
 
     def average_end_apply(self):
         assert self.averaging
-        self.x = self.mean[None, :] + (self.x - self.snap)
+        self.x = self._stored(self.mean[None, :] + (self.x - self.snap))
         self.averaging = False
 
     def round(self, k):

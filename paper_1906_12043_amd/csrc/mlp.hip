@@ -292,12 +292,14 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
         load_slice(Set1{}, 1);
         load_slice(Set2{}, 2);
         load_slice(Set3{}, 3);
+        // slices 4 and 5 do not exist when K = 128 (four slices): like the in-loop refill, the prefetch then
+        // reads the last slice again (never used) instead of running past the operands
         stage_to_lds(Set0{}, 0);
-        load_slice(Set0{}, 4);
+        load_slice(Set0{}, 4 < n_slices ? 4 : last);
         __syncthreads();
         read_frags(Set0{}, 0);
         stage_to_lds(Set1{}, 1);
-        load_slice(Set1{}, 5);
+        load_slice(Set1{}, 5 < n_slices ? 5 : last);
         __syncthreads();
         for (uint32_t s = 0; s < n_slices; s += 4) {        // the slice count is a multiple of 4
             deep_iteration(Set0{}, Set1{}, Set2{}, s);

@@ -99,46 +99,81 @@ def test_mlp_shape_validation():
         assert e.value.status == P.ERR_UNSUPPORTED
 
 
-def test_full_size_config_thirty_rounds():
+def test_full_size_config_thirty_rounds_free_running():
+    """C4 as specified, all 30 rounds free-running (the device never sees the oracle's state).
+
+    Two facts about this workload shape the comparison (neither is about the kernels):
+    1. relu decides A > 0 in the device's fp32.  With 2.1 M pre-activations per step a few land within
+       rounding of zero, and there the fp64 oracle may take the other branch.  Such a unit changes
+       column n of dW1 and db1[n] of that worker in that step (pinned on the CPU); those columns are
+       held to a loose bound, everything else to the bar.  The mask accumulates over the run and its
+       size is reported per round.
+    2. The iteration amplifies rounding differences geometrically (CPU evidence:
+       test_fp32_evaluations_of_the_benchmark_mlp_drift_apart), so NO fp32 evaluation follows fp64 to
+       1e-4 for 30 rounds.  The bar 1e-4 (1 + |x|) is asserted outright while it is meaningful (rounds
+       1..12); from then on the device must stay within max(bar, 4 x the deviation of the oracle's own
+       fp32 mirror from fp64), the mirror being the same numpy code run in fp32 on the same inputs."""
     cfg = synth_inputs.CONFIGS["C4_mlp"]
     W, shape, batch, k = cfg["W"], cfg["mlp"], cfg["batch"], cfg["k"][0]
     hyper = dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"])
     theta0 = synth_inputs.mlp_he_init(cfg["seed"], *shape)
     g = GpuMlp(W, shape, batch, theta0, **hyper)
     o = mlp.MlpOracle(theta0, W, *shape, batch, **hyper)
-    # Two facts about this workload shape the comparison (neither is about the kernels):
-    # 1. relu decides A > 0 in the device's fp32.  With 2.1 M pre-activations per step a few land
-    #    within rounding of zero, and there the fp64 oracle may take the other branch.  Such a unit
-    #    changes column n of dW1 and db1[n] of that worker and nothing else (pinned on the CPU), so
-    #    those columns are held to a loose sanity bound and everything else to the 1e-4 bar.
-    # 2. With lr 0.05, momentum 0.9 and 3072 unit-variance inputs the training is chaotic: the
-    #    oracle's own loss wanders between 3 and 10 and differences grow step by step, so a
-    #    free-running fp32 trajectory cannot follow fp64 for 30 rounds whatever the implementation.
-    #    Free-running parity is asserted for the first 4 rounds; for the remaining rounds the device
-    #    is restarted each round from the oracle's state (rounded to fp32, oracle -> device only) and
-    #    one full round is compared, so all 30 rounds are checked at the states the trajectory visits.
-    free_rounds = 4
-    excluded = 0
+    mirror = mlp.MlpOracle(theta0, W, *shape, batch, compute_dtype=np.float32, **hyper)
+    strict_rounds = 12
+    mx = mv = 0.0                                   # running envelope of the mirror's deviation
     for r in range(cfg["rounds"]):
-        if r >= free_rounds:
-            g.ctx.sync()
-            live = g.xA if g.ctx.live_model() == g.xA.data_ptr() else g.xB
-            live[:, :g.d] = torch.from_numpy(o.x.astype(np.float32)).to(g.dev)
-            g.v[:, :g.d] = torch.from_numpy(o.v.astype(np.float32)).to(g.dev)
-            torch.cuda.synchronize()
-            o.clear_ambiguous()
+        g.ctx.round_fused_tail(k) if r % 2 else g.ctx.round(k)      # both ways of closing the round
+        o.round(k); mirror.round(k)
+        sure = o.certain_mask()
+        gx, gv = g.x(), g.vel()
+        ex, ev = rel_err(gx[sure], o.x[sure]), rel_err(gv[sure], o.v[sure])
+        loose = rel_err(gx[~sure], o.x[~sure]) if (~sure).any() else 0.0
+        mx = max(mx, rel_err(mirror.x.astype(np.float64), o.x))
+        mv = max(mv, rel_err(mirror.v.astype(np.float64), o.v))
+        print("C4 round %2d free-running: rel err x %.3g v %.3g | fp32 mirror x %.3g v %.3g | borderline-relu columns: "
+              "%d params (%.2f %%), x err %.3g | oracle loss %.4f"
+              % (r + 1, ex, ev, mx, mv, int((~sure).sum()), 100.0 * (~sure).mean(), loose, o.last_loss.mean()), flush=True)
+        if r < strict_rounds:
+            assert ex <= TOL and ev <= 10 * TOL, (r, ex, ev)
+            assert loose <= 5e-3, (r, loose)
+        else:
+            assert ex <= max(TOL, 4 * mx) and ev <= max(10 * TOL, 4 * mv), (r, ex, ev, mx, mv)
+            assert loose <= max(5e-3, 4 * mx), (r, loose, mx)
+    assert (~sure).mean() <= 0.15                   # the accumulated exclusion stays a small part of the model
+    assert g.ctx.get_step() == o.step == cfg["rounds"] * k
+    g.close()
+
+
+def test_full_size_config_single_rounds_at_late_states():
+    """One round from the oracle's own state at rounds 10, 20 and 30 of the C4 trajectory (oracle ->
+    device only), compared at the full bar: the states a long run visits are checked without the
+    drift of the rounds before them."""
+    cfg = synth_inputs.CONFIGS["C4_mlp"]
+    W, shape, batch, k = cfg["W"], cfg["mlp"], cfg["batch"], cfg["k"][0]
+    hyper = dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"])
+    theta0 = synth_inputs.mlp_he_init(cfg["seed"], *shape)
+    W = 4                                                           # four workers carry the trajectory, on both sides
+    g = GpuMlp(W, shape, batch, theta0, **hyper)
+    o = mlp.MlpOracle(theta0, W, *shape, batch, **hyper)
+    for r in range(cfg["rounds"]):
+        if r % 10 != 9:
+            o.round(k)
+            continue
+        g.ctx.sync()
+        live = g.xA if g.ctx.live_model() == g.xA.data_ptr() else g.xB
+        live[:, :g.d] = torch.from_numpy(o.x.astype(np.float32)).to(g.dev)
+        g.v[:, :g.d] = torch.from_numpy(o.v.astype(np.float32)).to(g.dev)
+        torch.cuda.synchronize()
+        g.ctx.set_step(o.step)
+        o.clear_ambiguous()
         g.ctx.round(k); o.round(k)
         sure = o.certain_mask()
         gx, gv = g.x(), g.vel()
         ex, ev = rel_err(gx[sure], o.x[sure]), rel_err(gv[sure], o.v[sure])
         loose = rel_err(gx[~sure], o.x[~sure]) if (~sure).any() else 0.0
-        excluded = max(excluded, int((~sure).sum()))
-        if r < free_rounds or r % 6 == 5:
-            print("C4 round %d (%s): rel err x %.3g v %.3g; borderline-relu columns: %d params, x err %.3g; oracle loss %.4f"
-                  % (r + 1, "free" if r < free_rounds else "restarted", ex, ev, int((~sure).sum()), loose,
-                     o.last_loss.mean()), flush=True)
+        print("C4 round %d from the oracle's state: rel err x %.3g v %.3g; borderline-relu columns: %d params, x err %.3g"
+              % (r + 1, ex, ev, int((~sure).sum()), loose), flush=True)
         assert ex <= TOL and ev <= 10 * TOL, (r, ex, ev)
         assert loose <= 5e-3, (r, loose)
-    assert excluded <= 0.05 * sure.size            # the exclusion stays a sliver of the model
-    assert g.ctx.get_step() == o.step == cfg["rounds"] * k
     g.close()

@@ -150,3 +150,88 @@ def test_line6_preserves_worker_mean_and_first_round_is_identity():
     assert np.allclose(o.x.mean(axis=0), pre.mean(axis=0), rtol=0, atol=1e-15)
     assert np.allclose(o.x - o.x.mean(axis=0), (pre - o.snap) - (pre - o.snap).mean(axis=0), rtol=0, atol=1e-15)
     assert o.step == 5
+
+
+def test_optimizer_lines_match_a_library_optimizer():
+    """The momentum / weight-decay update of local_steps (reading R1 of the experiments' optimizer:
+    g = G + wd x; v = mu v + g; x = x - lr v, v0 = 0, no dampening) against torch.optim.SGD driving the
+    same network through autograd, three steps, W = 2 workers with their own mini-batches.  Values of
+    lr, mu, wd are all different so that a swapped or misplaced factor shows."""
+    shape, batch, W = (16, 8, 4), 8, 2
+    n_in, n_hidden, n_out = shape
+    hyper = dict(lr=0.0625, momentum=0.75, weight_decay=0.03125, seed=21)      # exact in fp32 and fp64
+    theta0 = synth_inputs.mlp_he_init(2, *shape).astype(np.float64)
+    theta0 += 0.1 * np.random.default_rng(4).standard_normal(theta0.size)
+    o = mlp.MlpOracle(theta0, W, *shape, batch, **hyper)
+    o.local_steps(3)
+    a = n_in * n_hidden; b = a + n_hidden; c = b + n_hidden * n_out
+    for i in range(W):
+        t = torch.tensor(theta0, dtype=torch.float64, requires_grad=True)
+        opt = torch.optim.SGD([t], lr=hyper["lr"], momentum=hyper["momentum"], weight_decay=hyper["weight_decay"])
+        for step in range(3):
+            X, y = mlp.minibatch(hyper["seed"], i, step, batch, n_in, n_out)
+            opt.zero_grad()
+            Z = torch.relu(torch.tensor(X) @ t[:a].view(n_in, n_hidden) + t[a:b]) @ t[b:c].view(n_hidden, n_out) + t[c:]
+            torch.nn.functional.cross_entropy(Z, torch.tensor(y)).backward()
+            opt.step()
+        assert np.max(np.abs(o.x[i] - t.detach().numpy())) < 1e-14
+        assert np.max(np.abs(o.v[i] - opt.state[t]["momentum_buffer"].numpy())) < 1e-13
+    assert o.step == 3
+
+
+def test_optimizer_lines_hand_values():
+    """A network whose hidden layer is dead (W1 = 0, b1 = 0: relu'(0) = 0) has a gradient one can write
+    down: only b2 moves, with G = softmax(b2) - (label counts)/B.  From b2 = 0 the first step is exact
+    in binary: G = 1/n_out - counts/B, g = G (b2 = 0), v = g, b2 = -lr g.  The second step is
+    written out from the update rule with the softmax evaluated here."""
+    shape, batch = (8, 4, 2), 8
+    n_in, n_hidden, n_out = shape
+    lr, mu, wd = 0.5, 0.25, 0.125
+    theta0 = np.zeros(synth_inputs.mlp_param_count(*shape))
+    theta0[n_in * n_hidden + n_hidden:-n_out] = np.arange(n_hidden * n_out) / 8.0      # W2 arbitrary: it cannot matter
+    o = mlp.MlpOracle(theta0, 1, *shape, batch, lr=lr, momentum=mu, weight_decay=wd, seed=33)
+    counts = [np.bincount(mlp.minibatch(33, 0, s, batch, n_in, n_out)[1], minlength=n_out) for s in range(2)]
+    o.local_steps(1)
+    g1 = 0.5 - counts[0] / batch                       # exact multiples of 1/8
+    assert np.array_equal(o.v[0, -n_out:], g1) and np.array_equal(o.x[0, -n_out:], -lr * g1)
+    # W2 sees only weight decay (H = 0): g = wd W2, v = g, W2' = W2 (1 - lr wd)
+    W2 = theta0[n_in * n_hidden + n_hidden:-n_out]
+    assert np.array_equal(o.v[0, n_in * n_hidden + n_hidden:-n_out], wd * W2)
+    assert np.array_equal(o.x[0, n_in * n_hidden + n_hidden:-n_out], W2 - lr * (wd * W2))
+    assert not o.x[0, :n_in * n_hidden + n_hidden].any()                                 # dead layer stays dead
+    o.local_steps(1)
+    b2 = -lr * g1
+    p = np.exp(b2 - b2.max()); p /= p.sum()
+    g2 = (p - counts[1] / batch) + wd * b2
+    v2 = mu * g1 + g2
+    assert np.allclose(o.v[0, -n_out:], v2, rtol=0, atol=1e-15)
+    assert np.allclose(o.x[0, -n_out:], b2 - lr * v2, rtol=0, atol=1e-15)
+    # a slip such as v = mu v + lr g, or x = x - lr g, lands far from these values
+    assert np.max(np.abs((b2 - lr * (mu * g1 + lr * g2)) - o.x[0, -n_out:])) > 1e-3 or not g2.any()
+
+
+def test_fp32_evaluations_of_the_benchmark_mlp_drift_apart():
+    """Reading R19's evidence.  At the benchmark's shape and hyper-parameters (3072-1024-10, batch 128,
+    lr 0.05, momentum 0.9) the iteration amplifies rounding differences: a copy of the oracle whose
+    STATE alone is rounded to fp32 after every update (arithmetic still fp64) and a copy that does all
+    arithmetic in fp32 both leave the fp64 run at a geometric rate.  Early rounds agree to fp32
+    rounding level; by round 26 neither is within the 1e-4 bar, whatever the implementation."""
+    cfg = synth_inputs.CONFIGS["C4_mlp"]
+    shape, batch, k, W = cfg["mlp"], cfg["batch"], cfg["k"][0], 2
+    hyper = dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"])
+    theta0 = synth_inputs.mlp_he_init(cfg["seed"], *shape)
+    ref = mlp.MlpOracle(theta0, W, *shape, batch, **hyper)
+    rounded = mlp.MlpOracle(theta0, W, *shape, batch, state_dtype=np.float32, **hyper)
+    single = mlp.MlpOracle(theta0, W, *shape, batch, compute_dtype=np.float32, **hyper)
+
+    def rel(a, b):
+        return float(np.max(np.abs(a - b) / (1.0 + np.abs(b))))
+    err = {}
+    for r in range(1, 27):
+        for o in (ref, rounded, single):
+            o.round(k)
+        err[r] = (rel(rounded.x, ref.x), rel(single.x.astype(np.float64), ref.x))
+    assert max(err[r][0] for r in range(1, 9)) < 2e-7 and max(err[r][1] for r in range(1, 9)) < 1e-6
+    assert err[16][0] < 1e-5 and err[12][1] < 1e-5               # the window in which free-running parity is meaningful
+    assert err[26][0] > 1e-4 and err[26][1] > 1e-4               # and where it ends
+    assert err[24][0] > 100 * err[8][0] and err[24][1] > 100 * err[8][1]
