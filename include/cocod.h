@@ -92,7 +92,9 @@ enum {
 typedef struct cocod_config {
     uint32_t struct_size;          /* sizeof(cocod_config); checked */
     uint32_t W;                    /* number of workers N of Algorithm 1, >= 1 */
-    uint64_t d;                    /* parameters per worker (sum of tensor sizes), >= 1, < 2^34 */
+    uint64_t d;                    /* parameters per worker (sum of tensor sizes), >= 1, < 2^34; and
+                                      W * ceil(d / 1024) <= 2^31 - 1 (blocks of one launch; tensors of a
+                                      list each round up on their own) */
     uint32_t n_tensors;            /* 0 or 1: one flat vector; else length of tensor_numel */
     uint32_t grad;                 /* cocod_grad_kind */
     const uint64_t *tensor_numel;  /* host, [n_tensors], each >= 1, sum == d; copied */
@@ -117,7 +119,13 @@ typedef struct cocod_config {
     const float *c;                /* device [W][stride]: centres (quadratic kind) */
     uint64_t stride;               /* elements between consecutive workers; >= padded_d, multiple of 4 */
     void *compute_stream;          /* hipStream_t for Step II and line 6 (NULL = the null stream) */
-    void *avg_stream;              /* hipStream_t for Step I; equal to compute_stream = no overlap */
+    void *avg_stream;              /* hipStream_t for Step I; equal to compute_stream = no overlap.
+                                      The share of the device that the averaging may occupy (the fraction a% of
+                                      the paper's time-speedup analysis) is a property of THIS stream and
+                                      therefore the caller's: create it with a compute-unit mask if the
+                                      platform allows.  The library offers no field for it: it never creates
+                                      streams, and on the machines this was built on the runtime refused
+                                      masked streams, so the setting could not be tested. */
     uint32_t mlp_in, mlp_hidden, mlp_out, mlp_batch;   /* MLP kind: layer widths and mini-batch size.  Supported
                                       shapes (else COCOD_ERR_UNSUPPORTED): mlp_in and mlp_batch multiples of 128,
                                       mlp_batch <= 1024, mlp_hidden a multiple of 64, 1 <= mlp_out <= 16,
@@ -178,6 +186,22 @@ int cocod_average_begin(cocod_ctx *ctx);
 int cocod_average_end_apply(cocod_ctx *ctx);
 
 /*
+ * Step I and line 6 in ONE pass over the models, with nothing overlapped: the weighted mean of the
+ * stored models is formed and x^i = x^_t + (x^i - x_t^i) applied by the same kernel (read x_t^i, read
+ * x^i, write x^i: 12 + 4/W bytes per parameter; the mean is still written to `mean`).  This is the
+ * sequential timeline that the paper's time-speedup analysis sets against the decoupled one
+ * (communication AFTER the k local steps instead of beside them); it exists to measure what the
+ * overlap buys.  Whatever schedule is set:
+ *   - while a round is open (after cocod_average_begin and any local steps) it closes the round;
+ *     if the overlapped schedule has already started the mean on avg_stream, compute_stream first
+ *     waits for it (same values, so the result does not change);
+ *   - while IDLE it is the blocking average of Local SGD: every worker is set to the weighted mean
+ *     of the live models (a round with zero local steps).
+ * Same bits as cocod_average_end_apply under any schedule.  Always ends IDLE.
+ */
+int cocod_average_apply_fused(cocod_ctx *ctx);
+
+/*
  * Step II and line 6 together: k local steps of which the LAST one applies line 6 to the model it
  * has just computed, before storing it (x = x^_t + ((x - gamma v) - x_t^i) in the step kernel's
  * registers), and closes the round.  Same arithmetic, in the same order, as
@@ -223,6 +247,8 @@ int cocod_external_step_bf16(cocod_ctx *ctx, const uint16_t *g, int close_round)
  * the eager calls may be mixed freely between rounds.  cocod_set_lr drops the recorded graphs (it
  * then waits for compute_stream).  Launches inside a graph are not seen by cocod_step_timing.
  * Only legal while IDLE (COCOD_ERR_STATE otherwise); k >= 0; needs a built-in gradient when k > 0.
+ * compute_stream must be a stream of the caller's own: the null stream cannot be captured, and a
+ * context created on it gets COCOD_ERR_INVALID here, before any GPU call.
  */
 int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail);
 

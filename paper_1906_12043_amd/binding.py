@@ -68,6 +68,7 @@ def lib():
             "cocod_graph_round": ([vp, i32, i32], i32),
             "cocod_average_begin": ([vp], i32),
             "cocod_average_end_apply": ([vp], i32),
+            "cocod_average_apply_fused": ([vp], i32),
             "cocod_set_schedule": ([vp, i32], i32),
             "cocod_set_lr": ([vp, C.c_float], i32),
             "cocod_get_step": ([vp, P(u64)], i32),
@@ -210,6 +211,9 @@ class Context:
 
     def average_end_apply(self):
         return cocod_average_end_apply(self.handle)
+
+    def average_apply_fused(self):
+        return _check(lib().cocod_average_apply_fused(self.handle), self.handle)
 
     def local_steps_end_apply(self, k):
         return _check(lib().cocod_local_steps_end_apply(self.handle, k), self.handle)

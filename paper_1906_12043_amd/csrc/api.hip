@@ -81,6 +81,8 @@ int hip_fail(cocod_ctx *ctx, hipError_t e, const char *what)
 // A mean vector up to this size is expected to stay in the 256 MB last-level cache while the W
 // workers of a line-6 step read it one after the other.
 constexpr uint64_t kMeanCacheBytes = 128ull << 20;
+// one grid dimension holds fewer than 2^32 threads: with 256-thread blocks, fewer than 2^24 blocks
+constexpr uint64_t kMaxBlocksPerGridDim = 1ull << 24;
 
 inline uint64_t round_up4(uint64_t n) { return (n + 3u) & ~static_cast<uint64_t>(3u); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -295,7 +297,12 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         }
         global += ctx->tensor_numel[t];
     }
-    if (ctx->chunks.size() * static_cast<uint64_t>(cfg->W) > 0x7fffffffull) {   // one block per (chunk, worker)
+    // Launch limits.  A grid dimension holds fewer than 2^32 THREADS, i.e. fewer than 2^24 blocks of 256: the
+    // (chunks, workers) grid of the step kernel needs chunks < 2^24 (implied by d < 2^34) and W <= 65535 (checked
+    // above).  The 1-D worker-fastest grid of the line-6 step puts chunks * W blocks into ONE dimension and is
+    // only used below that limit (see enqueue_step).  The total is capped as well, so that block counts stay
+    // inside 32-bit arithmetic everywhere.
+    if (ctx->chunks.size() * static_cast<uint64_t>(cfg->W) > 0x7fffffffull) {
         delete ctx;
         return fail(nullptr, COCOD_ERR_INVALID, "W * d is too large for one launch (more than 2^31 chunks of 1024 elements)");
     }
@@ -424,7 +431,9 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
         p.step_base = ctx->capturing ? ctx->d_step : nullptr;
-        p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes ? 1u : 0u;
+        // worker-fastest order: chunks * W blocks of 256 threads in one grid dimension, which holds < 2^32 threads
+        p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes &&
+                           ctx->chunks.size() * static_cast<uint64_t>(ctx->cfg.W) < kMaxBlocksPerGridDim ? 1u : 0u;
         // Step I inside the round's first step: that step reads exactly the stored models
         const bool head = ctx->schedule == COCOD_SCHED_HEAD && ctx->mean_pending && ctx->store_pending && !g_ext &&
                           !with_line6 && ctx->cfg.grad == COCOD_GRAD_QUADRATIC;
@@ -577,6 +586,32 @@ int cocod_average_end_apply(cocod_ctx *ctx)
     return COCOD_OK;
 }
 
+int cocod_average_apply_fused(cocod_ctx *ctx)
+{
+    if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
+    const bool opened_here = !ctx->averaging;
+    if (opened_here) {                   // blocking average of the live models: the stored models ARE the live ones
+        ctx->snap = ctx->live;
+        ctx->averaging = true;
+        ctx->mean_pending = true;
+    }
+    if (!ctx->dry) {
+        // a mean already running on the averaging stream (overlapped schedule) writes the same values to
+        // `mean`: let it finish first so that the two writers never overlap
+        if (!ctx->mean_pending && ctx->schedule == COCOD_SCHED_OVERLAP && ctx->s_avg != ctx->s_compute)
+            COCOD_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, ctx->ev_mean, 0));
+        for (size_t b = 0; b + 1 < ctx->bucket_begin.size(); ++b)
+            COCOD_HIP(ctx, cocod::launch_mean_correct(ctx->s_compute, ctx->live, ctx->snap, ctx->cfg.stride, ctx->cfg.W,
+                                                      ctx->bucket_begin[b], ctx->bucket_begin[b + 1], ctx->d_weights,
+                                                      ctx->cfg.mean));
+    }
+    ctx->averaging = false;
+    ctx->store_pending = false;
+    ctx->mean_pending = false;
+    ctx->snap = nullptr;
+    return COCOD_OK;
+}
+
 // Record one round into a graph.  Nothing executes; the context's state is put back afterwards.
 static int capture_round(cocod_ctx *ctx, int k, int fused_tail, hipGraphExec_t *exec)
 {
@@ -626,6 +661,9 @@ int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail)
     int rc = check_steps(ctx, k);
     if (rc == COCOD_OK && k > 0) rc = need_builtin_gradient(ctx);
     if (rc != COCOD_OK) return rc;
+    // stream capture cannot record the null stream (nor the legacy default stream handle)
+    if (!ctx->s_compute || ctx->s_compute == hipStreamLegacy)
+        return fail(ctx, COCOD_ERR_INVALID, "cocod_graph_round needs a compute stream of its own: the null stream cannot be captured");
     fused_tail = fused_tail != 0;
     if (ctx->dry) {                                  // state transitions only
         rc = cocod_average_begin(ctx);

@@ -56,7 +56,10 @@ int main(void)
     CHECK(cocod_live_model(ctx, &live) == COCOD_OK && live == cfg.xB);
     CHECK(cocod_average_end_apply(ctx) == COCOD_OK && cocod_is_averaging(ctx) == 0);
     CHECK(cocod_average_begin(ctx) == COCOD_OK && cocod_local_steps_end_apply(ctx, 3) == COCOD_OK);
-    CHECK(cocod_graph_round(ctx, 2, 1) == COCOD_OK);
+    CHECK(cocod_graph_round(ctx, 2, 1) == COCOD_ERR_INVALID);       /* the null stream cannot be captured */
+    CHECK(cocod_average_begin(ctx) == COCOD_OK && cocod_local_steps(ctx, 2) == COCOD_OK);
+    CHECK(cocod_average_apply_fused(ctx) == COCOD_OK && cocod_is_averaging(ctx) == 0);   /* closes the round */
+    CHECK(cocod_average_apply_fused(ctx) == COCOD_OK && cocod_is_averaging(ctx) == 0);   /* blocking average while idle */
     CHECK(cocod_get_step(ctx, &step) == COCOD_OK && step == 7);
     CHECK(cocod_set_schedule(ctx, COCOD_SCHED_HEAD) == COCOD_OK && cocod_set_schedule(ctx, 17) == COCOD_ERR_INVALID);
     CHECK(cocod_local_steps(ctx, -1) == COCOD_ERR_INVALID);

@@ -252,8 +252,38 @@ def test_external_step_state_machine():
         assert ctx.get_step() == 1
 
 
-def test_graph_round_state_machine():
+FAKE_STREAM = 0x40                 # dry-run contexts never touch their streams
+
+
+def test_graph_round_needs_a_capturable_stream():
+    for stream in (None, 1):                              # the null stream and the legacy default-stream handle
+        with dry(compute_stream=stream) as ctx:
+            with pytest.raises(P.CocodError) as e:
+                ctx.graph_round(1)
+            assert e.value.status == P.ERR_INVALID and "null stream" in str(e.value)
+            assert ctx.get_step() == 0 and not ctx.is_averaging()
+
+
+def test_average_apply_fused_state_machine():
     with dry() as ctx:
+        a = ctx.live_model()
+        ctx.average_apply_fused()                         # idle: blocking average, nothing rotates
+        assert not ctx.is_averaging() and ctx.live_model() == a and ctx.get_step() == 0
+        for sched in (P.SCHED_OVERLAP, P.SCHED_SERIAL, P.SCHED_FUSED, P.SCHED_HEAD):
+            ctx.set_schedule(sched)
+            ctx.average_begin()
+            ctx.local_steps(2)
+            ctx.average_apply_fused()                     # closes the open round under every schedule
+            assert not ctx.is_averaging()
+            with pytest.raises(P.CocodError) as e:
+                ctx.average_end_apply()
+            assert e.value.status == P.ERR_STATE
+        assert ctx.get_step() == 8
+    assert P.lib().cocod_average_apply_fused(None) == P.ERR_INVALID      # NULL context: an error, not a crash
+
+
+def test_graph_round_state_machine():
+    with dry(compute_stream=FAKE_STREAM, avg_stream=FAKE_STREAM) as ctx:
         a = ctx.live_model()
         ctx.graph_round(3, fused_tail=True)
         assert ctx.get_step() == 3 and not ctx.is_averaging() and ctx.live_model() != a
@@ -269,7 +299,7 @@ def test_graph_round_state_machine():
         with pytest.raises(P.CocodError) as e:
             ctx.graph_round(-1)
         assert e.value.status == P.ERR_INVALID
-    with dry(grad=P.GRAD_EXTERNAL, h=None, c=None) as ctx:
+    with dry(grad=P.GRAD_EXTERNAL, h=None, c=None, compute_stream=FAKE_STREAM) as ctx:
         with pytest.raises(P.CocodError) as e:
             ctx.graph_round(1)
         assert e.value.status == P.ERR_INVALID

@@ -448,3 +448,47 @@ def test_external_bf16_gradient_steps(packed, mu):
         check_state(g, o, what="bf16 external round %d" % r)
     assert g.ctx.get_step() == o.step
     g.close()
+
+
+@pytest.mark.parametrize("packed,weights", [(False, None), (True, None), (False, [0.1, 0.2, 0.3, 0.15, 0.25])])
+def test_average_apply_fused_matches_every_schedule_bit_for_bit(packed, weights):
+    """cocod_average_apply_fused (mean + line 6 in one pass, whatever schedule is set) against
+    cocod_average_end_apply under the fused schedule and under the overlapped one, and, while idle,
+    against a zero-step round (the blocking average of Local SGD); then against the oracle."""
+    W, k = 5, 2
+    sizes = [5, 4096, 1, 3, 8191, 64, 4097, 2] if packed else None
+    d = sum(sizes) if packed else 40_007
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=41, weights=weights)
+    h, c = synth_inputs.quadratic_data(15, W, d)
+    a = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)          # reference calls
+    b = GpuWorkers(W, d, h=h, c=c, tensor_numel=sizes, **hyper)          # the new call
+    o = orc.QuadraticOracle(h, c, **hyper)
+    for r, sched in enumerate((P.SCHED_FUSED, P.SCHED_OVERLAP, P.SCHED_SERIAL, P.SCHED_HEAD, P.SCHED_OVERLAP)):
+        a.ctx.set_schedule(P.SCHED_FUSED if r % 2 == 0 else P.SCHED_OVERLAP)
+        b.ctx.set_schedule(sched)
+        a.ctx.round(k)
+        b.ctx.average_begin(); b.ctx.local_steps(k); b.ctx.average_apply_fused()
+        o.round(k)
+        assert not b.ctx.is_averaging()
+        assert np.array_equal(a.x(), b.x()) and np.array_equal(a.vel(), b.vel()) and np.array_equal(a.avg(), b.avg()), sched
+    check_state(b, o, what="average_apply_fused")
+    a.ctx.local_steps(k); a.ctx.average_begin(); a.ctx.average_end_apply()      # Local SGD: steps, then blocking average
+    b.ctx.local_steps(k); b.ctx.average_apply_fused()
+    o.local_steps(k); o.average_begin(); o.average_end_apply()
+    assert np.array_equal(a.x(), b.x()) and np.array_equal(a.avg(), b.avg())
+    check_state(b, o, what="blocking average")
+    x = b.x()
+    assert all(np.array_equal(x[0], x[i]) for i in range(1, W))
+    a.close(); b.close()
+
+
+def test_graph_round_on_the_null_stream_is_refused_before_any_gpu_call():
+    W, d = 3, 5000
+    h, c = synth_inputs.quadratic_data(16, W, d)
+    g = GpuWorkers(W, d, h=h, c=c, two_streams="null", lr=0.05, momentum=0.9)
+    with pytest.raises(P.CocodError) as e:
+        g.ctx.graph_round(2)
+    assert e.value.status == P.ERR_INVALID
+    g.ctx.round(2)                                    # the context is still usable, and untouched by the refusal
+    assert g.ctx.get_step() == 2
+    g.close()
