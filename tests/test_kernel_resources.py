@@ -1,6 +1,7 @@
 """Build-time check (CPU only, cross-compiles for gfx950): no kernel of the library may use private
 scratch memory.  A register array that the compiler cannot keep in registers silently turns into
-extra memory traffic (caught once by the hardware counters in the fused mean + line-6 kernel)."""
+extra memory traffic (caught once by the hardware counters in the fused mean + line-6 kernel).
+The figures come from the compiler's own resource-usage remarks; nothing is written to disk."""
 import os
 import re
 import subprocess
@@ -9,23 +10,39 @@ from concurrent.futures import ThreadPoolExecutor
 from paper_1906_12043_amd import build as hip_build
 
 
-def _assembly(src):
-    cmd = [hip_build.HIPCC, *[f for f in hip_build.FLAGS if f != "-fPIC"], "-S", "--cuda-device-only",
-           os.path.join(hip_build.CSRC, src), "-o", "-"]
-    return subprocess.run(cmd, capture_output=True, text=True, check=True).stdout
+def _remarks(src):
+    cmd = [hip_build.HIPCC, *[f for f in hip_build.FLAGS if f != "-fPIC"], "-Rpass-analysis=kernel-resource-usage",
+           "--cuda-device-only", "-c", os.path.join(hip_build.CSRC, src), "-o", os.devnull]
+    return subprocess.run(cmd, capture_output=True, text=True, check=True).stderr
+
+
+def kernel_resources(src):
+    """{kernel name: {remark field: integer value}} of one source file."""
+    out, name = {}, None
+    for line in _remarks(src).splitlines():
+        m = re.search(r"remark:\s+(.*?):\s+(\S+) \[-Rpass-analysis=kernel-resource-usage\]", line)
+        if not m:
+            continue
+        field, value = m.group(1).strip(), m.group(2)
+        if field == "Function Name":
+            name = value
+            out[name] = {}
+        elif name is not None and value.lstrip("-").isdigit():
+            out[name][field] = int(value)
+    return out
 
 
 def test_no_kernel_uses_scratch_memory_or_spills():
     sources = [s for s in hip_build.SOURCES if s != "api.hip"]
     with ThreadPoolExecutor(max_workers=4) as pool:
-        texts = list(pool.map(_assembly, sources))
+        tables = list(pool.map(kernel_resources, sources))
     seen = 0
-    for src, text in zip(sources, texts):
-        names = re.findall(r"\.name:\s+(\S+)", text)
-        scratch = [int(v) for v in re.findall(r"\.private_segment_fixed_size:\s+(\d+)", text)]
-        spills = [int(v) for v in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)]
-        assert names and len(scratch) == len(spills) == len(names), src
-        for name, sc, sp in zip(names, scratch, spills):
-            assert sc == 0 and sp == 0, "%s: %s uses %d B scratch, %d spilled registers" % (src, name, sc, sp)
+    for src, table in zip(sources, tables):
+        assert table, src
+        for name, res in table.items():
+            # (scalar registers parked in vector-register lanes cost no memory traffic and are not counted)
+            assert res["ScratchSize [bytes/lane]"] == 0 and res["VGPRs Spill"] == 0, \
+                "%s: %s uses %d B scratch, %d spilled vector registers" % (
+                    src, name, res["ScratchSize [bytes/lane]"], res["VGPRs Spill"])
             seen += 1
     assert seen >= 20
