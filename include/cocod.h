@@ -294,6 +294,22 @@ int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[3], uint32_t launches
 int cocod_consensus_distance(cocod_ctx *ctx, double *result);
 
 /*
+ * cocod_consensus_distance for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same kernels and same bits, but
+ *   - the block partials live in a static device array of the library (2 MiB per GPU, held until the
+ *     process ends) instead of a buffer allocated on first use;
+ *   - the scalar goes to *result_device, DEVICE memory of the caller (one double, 8-byte aligned);
+ *   - the call only enqueues on compute_stream and returns: no wait, no copy, no allocation of any
+ *     kind (cocod_create has looked up the array's device address once for its GPU).
+ * Limit: at most 2^18 chunks of 1024 parameters per worker (tensors of a list round up each on their
+ * own), i.e. d up to 268 M for a flat model; beyond that COCOD_ERR_UNSUPPORTED.  All contexts on one
+ * GPU share the array: calls that overlap in time on one GPU (two streams, two threads) race on it and
+ * must be ordered by the caller; calls on one stream are ordered by the stream.  Nothing in the array
+ * has to be cleared between calls.
+ */
+int cocod_consensus_distance_noalloc(cocod_ctx *ctx, double *result_device);
+
+/*
  * Diagnostic (quadratic kind only): the objective of the paper's problem definition,
  * f(x) = sum_i p_i f_i(x) with f_i(x) = 1/2 sum_j h_ij (x_j - c_ij)^2, evaluated at the averaged
  * model x^ = sum_i p_i x^i of the live models, and || grad f(x^) ||^2, the quantity whose running

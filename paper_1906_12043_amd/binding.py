@@ -77,6 +77,7 @@ def lib():
             "cocod_is_averaging": ([vp], i32),
             "cocod_get_plan": ([vp, P(u64), P(u32), P(u32)], i32),
             "cocod_consensus_distance": ([vp, P(C.c_double)], i32),
+            "cocod_consensus_distance_noalloc": ([vp, vp], i32),
             "cocod_quadratic_objective": ([vp, P(C.c_double), P(C.c_double)], i32),
             "cocod_fill_quadratic": ([vp], i32),
             "cocod_mlp_workspace": ([vp, P(vp), P(vp), P(vp), P(vp), P(vp), P(u32)], i32),
@@ -283,6 +284,10 @@ class Context:
         out = C.c_double()
         _check(lib().cocod_consensus_distance(self.handle, C.byref(out)), self.handle)
         return out.value
+
+    def consensus_distance_noalloc(self, result_device):
+        """Enqueue the reduction; the scalar lands in the caller's device double."""
+        return _check(lib().cocod_consensus_distance_noalloc(self.handle, _addr(result_device)), self.handle)
 
     def quadratic_objective(self):
         """(f(x^), ||grad f(x^)||^2) at the weighted mean of the live models."""

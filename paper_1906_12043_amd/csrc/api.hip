@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -24,6 +25,7 @@ struct cocod_ctx {
     float *d_weights = nullptr;         // device copy of p_i (owned), nullptr = uniform
     float *d_sigma_w = nullptr;         // device copy of the per-worker noise scale (owned), nullptr = cfg.noise_sigma
     double *d_reduce = nullptr;         // scratch of the consensus-distance reduction (owned, allocated on first use)
+    double *static_scratch = nullptr;   // this GPU's copy of the library's static scratch array (not owned)
     float *mlp_ws = nullptr;            // MLP kind: work space (owned); mlp holds the pointers carved from it
     cocod::MlpParams mlp{};
     hipEvent_t ev_snap = nullptr;       // compute stream reached the point where the models are stored
@@ -53,6 +55,35 @@ struct cocod_ctx {
 };
 
 namespace {
+
+// Scratch of cocod_consensus_distance_noalloc: block partials of the reduction, in device memory that
+// exists from the moment the library is loaded, so the call never allocates.  One copy per GPU, held
+// until the process ends; every call on a GPU shares that GPU's copy.  In host code the array's name
+// is only a handle: the device address comes from hipGetSymbolAddress (scratch_for_current_device).
+constexpr uint32_t kNoAllocMaxChunks = 1u << 18;                       // 2^18 chunks of 1024 = 268 M parameters per worker
+static __device__ __align__(256) double scratch[2 + kNoAllocMaxChunks];   // result words, then one partial per chunk (2 MiB)
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices] = {};                               // device address of `scratch`, per device
+
+// Device address of this GPU's copy of `scratch`; looked up once per device, with that device current.
+hipError_t scratch_for_current_device(double **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        double *ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 thread_local std::string g_err;         // errors that have no context to live in
 
@@ -341,6 +372,7 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
                 ctx->mlp.y = reinterpret_cast<int32_t *>(at);
             }
         }
+        if (e == hipSuccess) e = scratch_for_current_device(&ctx->static_scratch);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_snap, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_mean, hipEventDisableTiming);
         if (e != hipSuccess) {
@@ -803,6 +835,24 @@ int cocod_consensus_distance(cocod_ctx *ctx, double *result)
                                                     ctx->cfg.W, ctx->d_weights, ctx->d_reduce + 2, ctx->d_reduce));
     COCOD_HIP(ctx, hipMemcpyAsync(result, ctx->d_reduce, sizeof(double), hipMemcpyDeviceToHost, ctx->s_compute));
     COCOD_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    return COCOD_OK;
+}
+
+int cocod_consensus_distance_noalloc(cocod_ctx *ctx, double *result_device)
+{
+    if (!ctx || !result_device) return fail(nullptr, COCOD_ERR_INVALID, "ctx and result_device must not be NULL");
+    if (reinterpret_cast<uintptr_t>(result_device) % sizeof(double) != 0)
+        return fail(ctx, COCOD_ERR_INVALID, "result_device must be 8-byte aligned");
+    const uint64_t n_chunks = ctx->chunks.size();
+    if (n_chunks > kNoAllocMaxChunks)
+        return fail(ctx, COCOD_ERR_UNSUPPORTED,
+                    "cocod_consensus_distance_noalloc: %llu chunks of 1024 parameters exceed the static scratch (%u chunks); "
+                    "use cocod_consensus_distance", (unsigned long long)n_chunks, kNoAllocMaxChunks);
+    if (ctx->dry) return COCOD_OK;
+    // Every partial the final pass reads is written by this call's first pass: nothing has to start at zero.
+    double *const partial = ctx->static_scratch + 2;
+    COCOD_HIP(ctx, cocod::launch_consensus_distance(ctx->s_compute, ctx->d_chunks, static_cast<uint32_t>(n_chunks), ctx->live,
+                                                    ctx->cfg.stride, ctx->cfg.W, ctx->d_weights, partial, result_device));
     return COCOD_OK;
 }
 

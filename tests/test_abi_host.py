@@ -344,3 +344,18 @@ def test_plain_c_client_of_the_abi(tmp_path):
     assert build.returncode == 0, build.stderr
     run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert run.returncode == 0 and "c abi client: ok" in run.stdout, run.stderr
+
+
+def test_no_alloc_consensus_distance_limits_on_the_host():
+    """The static scratch holds 2^18 block partials: a larger model is refused with a clear error (dry-run
+    contexts: no GPU call), a model at the limit is accepted."""
+    with dry(W=2, d=2**28) as ctx:                        # exactly 2^18 chunks
+        ctx.consensus_distance_noalloc(0x1000)
+    with dry(W=2, d=2**28 + 1) as ctx:
+        with pytest.raises(P.CocodError) as e:
+            ctx.consensus_distance_noalloc(0x1000)
+        assert e.value.status == P.ERR_UNSUPPORTED and "exceed the static scratch" in str(e.value)
+    with dry() as ctx:
+        with pytest.raises(P.CocodError) as e:
+            ctx.consensus_distance_noalloc(None)
+        assert e.value.status == P.ERR_INVALID
