@@ -69,11 +69,12 @@ def test_random_walk_over_the_state_machine(seed):
     W, d = 3, 2000
     big = W * d * 4
     ctx = P.Context(W=W, d=d, stride=d, lr=0.1, momentum=0.9, xA=base, xB=base + big, v=base + 2 * big, h=base + 3 * big,
-                    c=base + 4 * big, mean=base + 5 * big, flags=P.FLAG_DRY_RUN)
+                    c=base + 4 * big, mean=base + 5 * big, flags=P.FLAG_DRY_RUN,
+                    compute_stream=0x40, avg_stream=0x40)          # never touched by a dry-run context; graph rounds refuse the null stream
     m = RoundModel()
     g = base + 6 * big
     for _ in range(400):
-        op = rng.choice(["steps", "begin", "end", "tail", "ext", "ext_close", "graph", "sched", "lr"])
+        op = rng.choice(["steps", "begin", "end", "tail", "ext", "ext_close", "graph", "sched", "lr", "fused"])
         k = rng.choice([0, 0, 1, 1, 2, 3])
         try:
             if op == "steps":
@@ -91,6 +92,10 @@ def test_random_walk_over_the_state_machine(seed):
             elif op == "graph":
                 fused = rng.random() < 0.5
                 ctx.graph_round(k, fused); assert not m.open; m.begin(); m.steps(k); m.end()
+            elif op == "fused":                               # closes an open round, or is a blocking average while idle
+                ctx.average_apply_fused()
+                if m.open:
+                    m.end()
             elif op == "sched":
                 ctx.set_schedule(rng.choice([P.SCHED_OVERLAP, P.SCHED_SERIAL, P.SCHED_FUSED, P.SCHED_HEAD])); assert not m.open
             else:
