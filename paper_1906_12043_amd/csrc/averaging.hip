@@ -17,7 +17,10 @@
 namespace cocod {
 namespace {
 
-constexpr uint32_t kAvgThreads = 256;
+#ifndef COCOD_AVG_THREADS
+#define COCOD_AVG_THREADS 256
+#endif
+constexpr uint32_t kAvgThreads = COCOD_AVG_THREADS;
 constexpr int kRowBatch = 8;   // independent row loads in flight per thread
 
 typedef float f4v __attribute__((ext_vector_type(4)));

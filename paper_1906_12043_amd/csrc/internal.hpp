@@ -48,6 +48,16 @@ struct StepParams {
 hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start = nullptr,
                             hipEvent_t stop = nullptr);
 
+// The same step with one block per column tile of ALL workers, one wave per worker row (tile_step.hip).
+// p.mean_out set: the step also forms the mean of the models it reads (first step of a round); with
+// p.snap set as well (snap == x_in) it applies line 6 with that mean in the same pass (k = 1).
+// waves: worker rows per block (1..16); quads_per_lane: 1, 2 or 4 (tile of 256, 512 or 1024 columns).
+struct TileShape { uint32_t waves; int quads_per_lane; };
+hipError_t launch_tile_step(hipStream_t stream, const StepParams &p, const TileShape &shape,
+                            hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+// quads per lane (<= wanted) with which the mean-forming tile kernels fit W rows into LDS; 0 = W too large
+int tile_mean_quads_per_lane(uint32_t W, bool one_pass, int wanted);
+
 // mean[e] = sum_i p_i snap[i][e] for e in [begin, end) (both multiples of 4);
 // weights == nullptr means p_i = 1/W.
 hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, uint32_t W,

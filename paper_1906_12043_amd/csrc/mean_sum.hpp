@@ -14,31 +14,41 @@
 
 namespace cocod {
 
-struct MeanSum {
-    float s[4], c[4];
+// N independent element columns per thread: 4 for a thread that owns a 16-byte column quad, 1 for a
+// thread that owns a single element column.  The operations on one element are the same either way.
+template <int N>
+struct MeanSumN {
+    float s[N], c[N];
 
     __device__ __forceinline__ void clear()
     {
         #pragma unroll
-        for (int j = 0; j < 4; ++j) { s[j] = 0.0f; c[j] = 0.0f; }
+        for (int j = 0; j < N; ++j) { s[j] = 0.0f; c[j] = 0.0f; }
     }
 
-    // add p * (r0, r1, r2, r3); WEIGHTED == false means p == 1 and no multiply
+    // add p * r to element column j; WEIGHTED == false means p == 1 and no multiply
     template <bool WEIGHTED>
-    __device__ __forceinline__ void add(float p, float r0, float r1, float r2, float r3)
+    __device__ __forceinline__ void add_one(int j, float p, float r)
     {
         // No contraction in here: where the compiler knows c == 0 (first worker of an unrolled loop) it
         // turns the fused multiply-add into a plain product and would then fuse that product into the
         // subtraction below, which changes the bits of c from one kernel to the next.
         #pragma clang fp contract(off)
-        const float r[4] = {r0, r1, r2, r3};
-        #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float y = WEIGHTED ? __builtin_fmaf(p, r[j], -c[j]) : r[j] - c[j];
-            const float t = s[j] + y;
-            c[j] = (t - s[j]) - y;          // what the addition lost, with opposite sign
-            s[j] = t;
-        }
+        const float y = WEIGHTED ? __builtin_fmaf(p, r, -c[j]) : r - c[j];
+        const float t = s[j] + y;
+        c[j] = (t - s[j]) - y;          // what the addition lost, with opposite sign
+        s[j] = t;
+    }
+
+    // add p * (r0, r1, r2, r3) to a column quad
+    template <bool WEIGHTED>
+    __device__ __forceinline__ void add(float p, float r0, float r1, float r2, float r3)
+    {
+        static_assert(N == 4, "quad form");
+        add_one<WEIGHTED>(0, p, r0);
+        add_one<WEIGHTED>(1, p, r1);
+        add_one<WEIGHTED>(2, p, r2);
+        add_one<WEIGHTED>(3, p, r3);
     }
 
     // the mean: the weights already sum to one, or the sum is divided by W
@@ -48,9 +58,11 @@ struct MeanSum {
         if (!WEIGHTED) {
             const float inv = 1.0f / static_cast<float>(W);
             #pragma unroll
-            for (int j = 0; j < 4; ++j) s[j] *= inv;
+            for (int j = 0; j < N; ++j) s[j] *= inv;
         }
     }
 };
+
+using MeanSum = MeanSumN<4>;
 
 }  // namespace cocod

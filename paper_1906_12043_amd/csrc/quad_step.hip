@@ -23,6 +23,7 @@
 // Threads own consecutive blocks, so the missing normals are the right-hand neighbour's: three
 // cross-lane moves (one LDS word across a wave boundary) instead of a second generator call.
 #include "internal.hpp"
+#include "step_common.hpp"
 #include "philox.hpp"
 #include "mean_sum.hpp"
 
@@ -30,26 +31,6 @@
 
 namespace cocod {
 namespace {
-
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-
-constexpr int kAuxNonTemporal = 2;   // cache-policy bits of the buffer instructions: nt
-
-// Raw buffer descriptor over `bytes` bytes starting at p (stride 0, 32-bit data format).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const float *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p), 0, static_cast<int>(bytes), 0x00020000);
-}
-__device__ __forceinline__ f4 load_quad(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
-{
-    return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, static_cast<int>(byte_off), 0, kAuxNonTemporal));
-}
-__device__ __forceinline__ void store_quad(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f4 a)
-{
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, a), r, static_cast<int>(byte_off), 0, kAuxNonTemporal);
-}
 
 // Four normals for a thread's memory quad whose first element has global index 4*q + shift.
 // shift == 0: the quad is one generator block.  Otherwise the quad takes the last 4 - shift normals
@@ -90,8 +71,7 @@ __device__ __forceinline__ f4 noise_for_quad(uint64_t q, uint32_t shift, const S
 // TAIL: 0 = plain local step; 1 = last step of a round with line 6 applied to the fresh model
 // before it is stored, x = mean + ((x - gamma v) - snap); 2 = the same when the step reads the
 // stored models themselves (k = 1: snap is x_in, no extra read).
-// GRAD: where the stochastic gradient G comes from.
-enum { kGradQuadNoisy = 0, kGradQuadExact = 1, kGradExternal = 2, kGradExternalBf16 = 3 };
+// GRAD: where the stochastic gradient G comes from (step_common.hpp).
 
 template <bool HAS_V, int GRAD, int TAIL>
 __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParams p)
@@ -117,20 +97,20 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
     const uint32_t off = e * 4;
     const f4 x0 = load_quad(rx_in, off);
     const f4 v0 = HAS_V ? load_quad(rv, off) : f4{0.f, 0.f, 0.f, 0.f};
-    f4 g;
+    constexpr bool QUADRATIC = GRAD == kGradQuadNoisy || GRAD == kGradQuadExact;
+    f4 a, c = f4{0.f, 0.f, 0.f, 0.f};                     // a: curvature h, or the caller's gradient
     if (GRAD == kGradExternal) {                          // caller's gradient: read x, v, g; write x, v (20 B)
-        g = load_quad(make_rsrc(p.g + row, bytes), off);
+        a = load_quad(make_rsrc(p.g + row, bytes), off);
     } else if (GRAD == kGradExternalBf16) {               // the same with 16-bit gradients (18 B): a brain float
         const uint16_t *gb = reinterpret_cast<const uint16_t *>(p.g) + row;     // is the upper half of an fp32
         const __amdgpu_buffer_rsrc_t rg =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(gb), 0, static_cast<int>(bytes / 2), 0x00020000);
         const u2 w = __builtin_amdgcn_raw_buffer_load_b64(rg, static_cast<int>(off / 2), 0, kAuxNonTemporal);
-        g = f4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
+        a = f4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
                __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u)};
     } else {
-        const f4 h = load_quad(make_rsrc(p.h + row, bytes), off);
-        const f4 c = load_quad(make_rsrc(p.c + row, bytes), off);
-        g = h * (x0 - c);
+        a = load_quad(make_rsrc(p.h + row, bytes), off);
+        c = load_quad(make_rsrc(p.c + row, bytes), off);
     }
     f4 snap = x0, mean = f4{0.f, 0.f, 0.f, 0.f};
     if (TAIL == 1) snap = load_quad(make_rsrc(p.snap + row, bytes), off);
@@ -140,13 +120,12 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_kernel(const StepParam
         mean = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rm, static_cast<int>(off), 0, 0));
     }
 
-    if (GRAD == kGradQuadNoisy)
-        g += (p.sigma_w ? p.sigma_w[worker] : p.sigma) * noise_for_quad((ck.glob_off >> 2) + threadIdx.x, shift, p, worker);
-    g += p.weight_decay * x0;
-    f4 v = v0;
-    if (HAS_V) { v = p.momentum * v0 + g; g = v; }
-    f4 x = x0 - p.lr * g;
-    if (TAIL != 0) x = mean + (x - snap);
+    f4 z = f4{0.f, 0.f, 0.f, 0.f};
+    if (GRAD == kGradQuadNoisy) z = noise_for_quad((ck.glob_off >> 2) + threadIdx.x, shift, p, worker);
+    const float sigma = GRAD == kGradQuadNoisy ? (p.sigma_w ? p.sigma_w[worker] : p.sigma) : 0.0f;
+    f4 x, v;
+    local_step_quad<HAS_V, QUADRATIC, GRAD == kGradQuadNoisy, TAIL != 0>(x, v, x0, v0, a, c, z, sigma, p.lr, p.momentum,
+                                                                          p.weight_decay, snap, mean);
 
     if (e + 4 > ck.n && e < ck.n) {                       // tensor tail: alignment pads keep their old values
         const uint32_t keep = ck.n - e;                   // 1..3 real elements
@@ -202,13 +181,12 @@ __global__ __launch_bounds__(kStepThreads) void quad_step_head_kernel(const Step
         if (w + DEPTH < p.W) ring[j] = load_row(w + DEPTH);
         acc.add<WEIGHTED>(WEIGHTED ? p.weights[w] : 1.0f, cur.x.x, cur.x.y, cur.x.z, cur.x.w);
 
-        f4 g = cur.h * (cur.x - cur.c);
-        if (GRAD == kGradQuadNoisy)
-            g += (p.sigma_w ? p.sigma_w[w] : p.sigma) * noise_for_quad(q, shift, p, w, w);
-        g += p.weight_decay * cur.x;
-        f4 v = cur.v;
-        if (HAS_V) { v = p.momentum * cur.v + g; g = v; }
-        f4 x = cur.x - p.lr * g;
+        f4 z = f4{0.f, 0.f, 0.f, 0.f};
+        if (GRAD == kGradQuadNoisy) z = noise_for_quad(q, shift, p, w, w);
+        const float sigma = GRAD == kGradQuadNoisy ? (p.sigma_w ? p.sigma_w[w] : p.sigma) : 0.0f;
+        f4 x, v;
+        local_step_quad<HAS_V, true, GRAD == kGradQuadNoisy, false>(x, v, cur.x, cur.v, cur.h, cur.c, z, sigma, p.lr, p.momentum,
+                                                                   p.weight_decay, cur.x, cur.x);
         if (e + 4 > ck.n && e < ck.n) {                   // tensor tail: alignment pads keep their old values
             const uint32_t keep = ck.n - e;
             if (keep < 2) { x.y = cur.x.y; v.y = cur.v.y; }
