@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcocod.so")
-SOURCES = ["api.hip", "quad_step.hip", "tile_step.hip", "averaging.hip", "fill.hip", "mlp.hip"]
+SOURCES = ["api.hip", "local_step.hip", "averaging.hip", "fill.hip", "mlp.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for all device code (scalar fp32 only)
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",

@@ -109,27 +109,13 @@ int hip_fail(cocod_ctx *ctx, hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);         \
     } while (0)
 
-// Which kernel serves each kind of local step.  tile = one block per column tile of all workers
-// (tile_step.hip) with `waves` worker rows per block and `quads` 16-byte quads per lane; otherwise the
-// row-per-block kernel of quad_step.hip (and its column-walking variant for the mean-forming first step).
-struct StepChoice { int tile; uint32_t waves; int quads; };
-enum { kStepPlain = 0, kStepTail = 1, kStepHead = 2, kStepOnePass = 3, kStepKinds = 4 };
-StepChoice g_choice[kStepKinds] = {
-    {1, 1, 1},      // plain step: single-wave blocks stream fastest (measured 6.6 against 6.05 TB/s for 4-wave blocks)
-    {1, 1, 1},      // step that carries line 6
-    {1, 16, 1},     // first step of a round that forms the mean
-    {1, 16, 1},     // k = 1: mean, step and line 6 in one pass (tile kernel only; 0 = not used)
-};
-
-#ifdef COCOD_TUNING
-int g_force_worker_fastest = -1;
-#endif
-
 // A mean vector up to this size is expected to stay in the 256 MB last-level cache while the W
 // workers of a line-6 step read it one after the other.
 constexpr uint64_t kMeanCacheBytes = 128ull << 20;
 // one grid dimension holds fewer than 2^32 threads: with 256-thread blocks, fewer than 2^24 blocks
 constexpr uint64_t kMaxBlocksPerGridDim = 1ull << 24;
+// the mean-forming steps launch up to four 1024-thread blocks per chunk in one grid dimension
+constexpr uint64_t kMaxChunksMeanStep = 1ull << 20;
 
 inline uint64_t round_up4(uint64_t n) { return (n + 3u) & ~static_cast<uint64_t>(3u); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -429,9 +415,8 @@ int cocod_sync(cocod_ctx *ctx)
 static bool one_pass_applies(const cocod_ctx *ctx)
 {
     return ctx->schedule == COCOD_SCHED_HEAD && ctx->mean_pending && ctx->store_pending &&
-           ctx->cfg.grad == COCOD_GRAD_QUADRATIC && g_choice[kStepOnePass].tile &&
-           ctx->chunks.size() * 4ull * 1024ull < (1ull << 32) &&
-           cocod::tile_mean_quads_per_lane(ctx->cfg.W, true, g_choice[kStepOnePass].quads) != 0;
+           ctx->cfg.grad == COCOD_GRAD_QUADRATIC && cocod::local_step_mean_quads_per_lane(ctx->cfg.W, true) != 0 &&
+           ctx->chunks.size() < kMaxChunksMeanStep;
 }
 
 // One local step on the compute stream; with_line6 fuses line 6 into it (last step of a round).
@@ -489,23 +474,18 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
         p.step_base = ctx->capturing ? ctx->d_step : nullptr;
-        // worker-fastest order: chunks * W blocks of 256 threads in one grid dimension, which holds < 2^32 threads
+        // worker-fastest order: 4 * chunks * W single-wave blocks in one grid dimension, which holds < 2^32 threads
         p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes &&
                            ctx->chunks.size() * static_cast<uint64_t>(ctx->cfg.W) < kMaxBlocksPerGridDim ? 1u : 0u;
-#ifdef COCOD_TUNING
-        if (g_force_worker_fastest >= 0) p.worker_fastest = static_cast<uint32_t>(g_force_worker_fastest);
-#endif
-        // Step I inside the round's first step: that step reads exactly the stored models
+        // Step I inside the round's first step: that step reads exactly the stored models (when there are
+        // too many workers for its LDS tile, the mean stays pending and is formed just before line 6)
         const bool head = ctx->schedule == COCOD_SCHED_HEAD && ctx->mean_pending && ctx->store_pending && !g_ext &&
-                          !with_line6 && ctx->cfg.grad == COCOD_GRAD_QUADRATIC;
-        if (head) {
-            p.mean_out = ctx->cfg.mean;
-            p.weights = ctx->d_weights;
-            ctx->mean_pending = false;
-        }
+                          !with_line6 && ctx->cfg.grad == COCOD_GRAD_QUADRATIC &&
+                          cocod::local_step_mean_quads_per_lane(ctx->cfg.W, false) != 0 &&
+                          ctx->chunks.size() < kMaxChunksMeanStep;
         // k = 1 under the same schedule: mean, step and line 6 in one pass over the stored models
         const bool one_pass = with_line6 && !g_ext && one_pass_applies(ctx);
-        if (one_pass) {
+        if (head || one_pass) {
             p.mean_out = ctx->cfg.mean;
             p.weights = ctx->d_weights;
             ctx->mean_pending = false;
@@ -517,18 +497,7 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
             ctx->t_kind[ctx->t_used] = head ? 2 : (with_line6 ? 1 : 0);
             ctx->t_used += 1;
         }
-        const int kind = one_pass ? kStepOnePass : head ? kStepHead : with_line6 ? kStepTail : kStepPlain;
-        bool tile = g_choice[kind].tile != 0;
-        if (head && tile && cocod::tile_mean_quads_per_lane(ctx->cfg.W, false, g_choice[kind].quads) == 0)
-            tile = false;                                  // too many workers for the LDS tile: the column-walking kernel
-        // tiles * threads per block must stay below 2^32 threads in the grid's x dimension (a tile is at least 256 columns)
-        if (tile && !one_pass && ctx->chunks.size() * 4ull * 1024ull >= (1ull << 32)) tile = false;
-        if (tile) {
-            const cocod::TileShape shape{g_choice[kind].waves, g_choice[kind].quads};
-            COCOD_HIP(ctx, cocod::launch_tile_step(ctx->s_compute, p, shape, t0, t1));
-        } else {
-            COCOD_HIP(ctx, cocod::launch_quad_step(ctx->s_compute, p, t0, t1));
-        }
+        COCOD_HIP(ctx, cocod::launch_local_step(ctx->s_compute, p, t0, t1));
     }
     if (ctx->store_pending) {
         ctx->spare = ctx->live;
@@ -949,17 +918,6 @@ int cocod_fill_quadratic(cocod_ctx *ctx)
                                                 static_cast<uint32_t>(ctx->cfg.seed >> 32)));
     return COCOD_OK;
 }
-
-#ifdef COCOD_TUNING
-// Tuning builds only: choose the kernel and launch shape of a step kind (see g_choice).
-int cocod_debug_tune(int kind, int tile, int waves, int quads)
-{
-    if (kind == 99) { g_force_worker_fastest = tile; return COCOD_OK; }
-    if (kind < 0 || kind >= kStepKinds) return COCOD_ERR_INVALID;
-    g_choice[kind] = StepChoice{tile, static_cast<uint32_t>(waves), quads};
-    return COCOD_OK;
-}
-#endif
 
 int cocod_debug_copy(void *stream, const float *src, float *dst, uint64_t n)
 {

@@ -44,19 +44,17 @@ struct StepParams {
     const float *weights;      //           (Step I inside Step II's first pass); p_i, nullptr = 1/W
 };
 
-// start / stop: optional events that receive the kernel's own begin / end timestamps
-hipError_t launch_quad_step(hipStream_t stream, const StepParams &p, hipEvent_t start = nullptr,
-                            hipEvent_t stop = nullptr);
-
-// The same step with one block per column tile of ALL workers, one wave per worker row (tile_step.hip).
-// p.mean_out set: the step also forms the mean of the models it reads (first step of a round); with
-// p.snap set as well (snap == x_in) it applies line 6 with that mean in the same pass (k = 1).
-// waves: worker rows per block (1..16); quads_per_lane: 1, 2 or 4 (tile of 256, 512 or 1024 columns).
-struct TileShape { uint32_t waves; int quads_per_lane; };
-hipError_t launch_tile_step(hipStream_t stream, const StepParams &p, const TileShape &shape,
-                            hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
-// quads per lane (<= wanted) with which the mean-forming tile kernels fit W rows into LDS; 0 = W too large
-int tile_mean_quads_per_lane(uint32_t W, bool one_pass, int wanted);
+// One local step of all W workers (local_step.hip).  The kind of step follows from the parameters:
+//   snap == nullptr, mean_out == nullptr   plain step
+//   snap set                               last step of a round, line 6 applied to its result
+//   mean_out set                           first step of a round that also forms the mean of the models it reads
+//   mean_out and snap (== x_in) set        k = 1: mean, step and line 6 in one pass
+// start / stop: optional events that receive the kernel's own begin / end timestamps.
+hipError_t launch_local_step(hipStream_t stream, const StepParams &p, hipEvent_t start = nullptr,
+                             hipEvent_t stop = nullptr);
+// Column quads per lane (1 or 2) with which the mean-forming steps hold the W rows of a tile in LDS;
+// 0 = W is too large for them (the mean is then formed by a pass of its own).
+int local_step_mean_quads_per_lane(uint32_t W, bool one_pass);
 
 // mean[e] = sum_i p_i snap[i][e] for e in [begin, end) (both multiples of 4);
 // weights == nullptr means p_i = 1/W.

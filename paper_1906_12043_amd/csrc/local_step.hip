@@ -1,23 +1,32 @@
-// Local-step kernels of Algorithm 1 (CoCoD-SGD) in which ONE BLOCK SERVES ONE COLUMN TILE OF ALL W
-// WORKERS, one wave per worker row.  Same arithmetic per parameter as quad_step.hip:
-//     G = h_ij (x_j - c_ij) + sigma z(seed, i, t, j) ;  g = G + lambda x ;  v = mu v + g ;  x = x - gamma v
-// What the worker-tile shape buys is everything that couples the W workers of a column:
-//   HEAD      the round's first step also forms Step I's weighted mean of the models it reads: every
-//             wave puts its row's tile into LDS, the block sums the tile's columns over the workers
-//             in order 0..W-1 (the one compensated sum of mean_sum.hpp, so the bits equal those of
-//             the stand-alone mean kernel) and stores the mean: 4/W bytes per parameter instead of a
-//             pass of its own, while each wave streams its row as the row-per-block step does.
-//   TAIL      the round's last step applies line 6, x = mean + (x_new - x_stored): the W waves of a
-//             block read the same piece of the mean at the same time, so it crosses the L2 boundary
-//             once per tile instead of once per worker.
+// Step II of Algorithm 1 (CoCoD-SGD) for the synthetic quadratic workers and for a caller's gradient:
+// one fused local step.  Per parameter j of worker i at global step t
+//     G = h_ij (x_j - c_ij) + sigma z(seed, i, t, j)        stochastic gradient (or the caller's g)
+//     g = G + lambda x ;  v = mu v + g ;  x = x - gamma v    momentum SGD of the experiments
+// The gradient is never written to memory: the kernel reads x, v, h, c and writes x, v (24 bytes per
+// parameter; 16 when mu = 0 and v is untouched; 20 / 18 with a caller's fp32 / 16-bit gradient).
+//
+// Work decomposition.  A tile is Q x 64 consecutive 16-byte quads of one tensor (Q = 1 or 2: four or
+// two tiles per 1024-element chunk of the chunk table, which maps a block to its tensor slice, so one
+// launch covers a whole parameter list); a WAVE serves one tile of one worker row and moves Q
+// contiguous KiB per array.  Every wave is self-contained (its noise too: the generator block of the
+// right-hand neighbour, needed when a tensor starts at a global index that is not a multiple of 4,
+// comes from the next lane or the wave's own next pass), so block shape is free:
+//   PLAIN / TAIL   single-wave blocks, grid (tiles, workers).  Measured on MI355X at W = 16, d = 11.2 M:
+//             6.6 TB/s against 6.05 TB/s for the same step in 4-wave blocks and 5.8 in 16-wave blocks;
+//             small independent blocks stream best on this chip.  TAIL is the round's last step
+//             with line 6 applied to the fresh model before it is stored, x = mean + (x_new - x_stored).
+//   HEAD      the round's first step also forms Step I's weighted mean of the models it reads.  One
+//             block = one tile of ALL W workers, one wave per worker row (16 rows at a time): every wave
+//             puts its row's tile into LDS, the block sums the tile's columns over the workers in order
+//             0..W-1 (the one compensated sum of mean_sum.hpp, so the bits equal those of the stand-alone
+//             mean kernel) and stores the mean: 4/W bytes per parameter instead of a pass of its own.
 //   ONE_PASS  k = 1: Step I, the local step and line 6 in a single sweep (24 + 4/W bytes per
-//             parameter): the step reads the stored models, forms their mean through LDS as HEAD
-//             does, and applies line 6 with that mean before anything is stored.
-// A tile is Q x 64 column quads (Q = 1, 2 or 4 per lane; four tiles, two or one per 1024-element
-// chunk of the chunk table); a wave moves Q contiguous KiB per array.  Each wave is self-contained
-// (its noise, too: the generator block of the right-hand neighbour, needed when a tensor starts at a
-// global index that is not a multiple of 4, comes from the next lane or the wave's own next pass),
-// so the only block-wide synchronisation is around the LDS tile of the mean-forming modes.
+//             parameter): as HEAD, and line 6 is applied with the tile's mean before anything is stored.
+//
+// Memory path: every model array is streamed exactly once per step and is far larger than the caches,
+// so all accesses carry the non-temporal hint and go through buffer instructions whose descriptor
+// covers exactly the tile (step_common.hpp).  The mean is shared by the W workers of a column and is
+// read with an ordinary cached load.
 #include "internal.hpp"
 #include "step_common.hpp"
 #include "philox.hpp"
@@ -69,7 +78,7 @@ __device__ __forceinline__ void noise_for_lane(f4 (&z)[Q], uint64_t q0, uint32_t
 // mean-forming modes: 1, the block loops over its worker groups itself).
 // Dynamic LDS (mean-forming modes only): W rows of the tile, then (ONE_PASS) the tile of the mean.
 template <bool HAS_V, int GRAD, int MODE, bool WEIGHTED, int NWMAX, int Q>
-__global__ __launch_bounds__(64 * NWMAX) void tile_step_kernel(const StepParams p)
+__global__ __launch_bounds__(64 * NWMAX) void local_step_kernel(const StepParams p)
 {
     constexpr bool FORMS_MEAN = MODE == kModeHead || MODE == kModeOnePass;
     constexpr bool LINE6 = MODE == kModeTail || MODE == kModeTailIn || MODE == kModeOnePass;
@@ -245,7 +254,7 @@ template <bool HAS_V, int GRAD, int MODE, bool WEIGHTED, int NWMAX, int Q>
 hipError_t launch_one(hipStream_t stream, const StepParams &p, uint32_t waves, hipEvent_t start, hipEvent_t stop)
 {
     constexpr bool FORMS_MEAN = MODE == kModeHead || MODE == kModeOnePass;
-    auto kernel = tile_step_kernel<HAS_V, GRAD, MODE, WEIGHTED, NWMAX, Q>;
+    auto kernel = local_step_kernel<HAS_V, GRAD, MODE, WEIGHTED, NWMAX, Q>;
     size_t lds = 0;
     if (FORMS_MEAN) {
         lds = (static_cast<size_t>(p.W) + (MODE == kModeOnePass ? 1 : 0)) * Q * 256 * sizeof(float);
@@ -284,49 +293,42 @@ hipError_t launch_grad(hipStream_t stream, const StepParams &p, uint32_t waves, 
                  : launch_one<false, kGradQuadExact, MODE, WEIGHTED, NWMAX, Q>(stream, p, waves, start, stop);
 }
 
-template <int MODE, int NWMAX>
-hipError_t launch_q(hipStream_t stream, const StepParams &p, uint32_t waves, int q, hipEvent_t start, hipEvent_t stop)
+// Launch shapes (measured on MI355X, see the file header): single-wave blocks with one quad per lane
+// for the steps whose waves are independent; for the mean-forming steps sixteen worker rows per block,
+// one quad per lane up to W = 16 and two above (fewer, larger blocks when every wave serves several rows).
+template <int MODE>
+hipError_t launch_mode(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
     constexpr bool FORMS_MEAN = MODE == kModeHead || MODE == kModeOnePass;
-    const bool weighted = FORMS_MEAN && p.weights != nullptr;
-#define COCOD_TILE_Q(QQ)                                                                                     \
-    (weighted ? launch_grad<MODE, FORMS_MEAN, NWMAX, QQ>(stream, p, waves, start, stop)                     \
-              : launch_grad<MODE, false, NWMAX, QQ>(stream, p, waves, start, stop))
-    // four quads per lane only where the registers of a 16-wave block hold them: the plain step
-    if constexpr (MODE == kModePlain) { if (q >= 4) return COCOD_TILE_Q(4); }
-    if (q >= 2) return COCOD_TILE_Q(2);
-    return COCOD_TILE_Q(1);
-#undef COCOD_TILE_Q
+    if constexpr (!FORMS_MEAN) {
+        return launch_grad<MODE, false, 1, 1>(stream, p, 1, start, stop);
+    } else {
+        const uint32_t waves = p.W < 16u ? p.W : 16u;
+        const int q = local_step_mean_quads_per_lane(p.W, MODE == kModeOnePass);
+        if (q == 0) return hipErrorInvalidValue;
+        if (p.weights) return q == 2 ? launch_grad<MODE, true, 16, 2>(stream, p, waves, start, stop)
+                                     : launch_grad<MODE, true, 16, 1>(stream, p, waves, start, stop);
+        return q == 2 ? launch_grad<MODE, false, 16, 2>(stream, p, waves, start, stop)
+                      : launch_grad<MODE, false, 16, 1>(stream, p, waves, start, stop);
+    }
 }
 
 }  // namespace
 
-// Quads per lane for a mean-forming launch: the W rows of the tile (and the mean's, in one-pass mode)
-// must fit the LDS budget.  0 = W is too large for these kernels.
-int tile_mean_quads_per_lane(uint32_t W, bool one_pass, int wanted)
+int local_step_mean_quads_per_lane(uint32_t W, bool one_pass)
 {
-    for (int q = wanted >= 2 ? 2 : 1; q >= 1; q >>= 1)
-        if ((static_cast<size_t>(W) + (one_pass ? 1 : 0)) * q * 256 * sizeof(float) <= kTileLdsMax) return q;
+    const size_t rows = static_cast<size_t>(W) + (one_pass ? 1 : 0);       // the W model rows, and the mean's in one-pass mode
+    if (W > 16 && rows * 2 * 256 * sizeof(float) <= kTileLdsMax) return 2;
+    if (rows * 256 * sizeof(float) <= kTileLdsMax) return 1;
     return 0;
 }
 
-hipError_t launch_tile_step(hipStream_t stream, const StepParams &p, const TileShape &shape, hipEvent_t start, hipEvent_t stop)
+hipError_t launch_local_step(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)
 {
-    const bool forms_mean = p.mean_out != nullptr;
-    const uint32_t max_waves = 16;
-    uint32_t waves = shape.waves < 1 ? 1 : (shape.waves > max_waves ? max_waves : shape.waves);
-    if (waves > p.W) waves = p.W;
-    int q = shape.quads_per_lane;
-    if (forms_mean) {
-        q = tile_mean_quads_per_lane(p.W, p.snap != nullptr, q);
-        if (q == 0) return hipErrorInvalidValue;
-        if (p.snap) return launch_q<kModeOnePass, 16>(stream, p, waves, q, start, stop);
-        return launch_q<kModeHead, 16>(stream, p, waves, q, start, stop);
-    }
-    if (!p.snap)            return waves == 1 ? launch_q<kModePlain, 1>(stream, p, 1, q, start, stop)
-                                              : launch_q<kModePlain, 16>(stream, p, waves, q, start, stop);
-    if (p.snap != p.x_in)   return launch_q<kModeTail, 16>(stream, p, waves, q, start, stop);
-    return launch_q<kModeTailIn, 16>(stream, p, waves, q, start, stop);
+    if (p.mean_out) return p.snap ? launch_mode<kModeOnePass>(stream, p, start, stop) : launch_mode<kModeHead>(stream, p, start, stop);
+    if (!p.snap) return launch_mode<kModePlain>(stream, p, start, stop);
+    if (p.snap != p.x_in) return launch_mode<kModeTail>(stream, p, start, stop);
+    return launch_mode<kModeTailIn>(stream, p, start, stop);
 }
 
 }  // namespace cocod

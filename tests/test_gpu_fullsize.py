@@ -123,6 +123,11 @@ def test_resnet18_size_fifty_rounds_sampled_graph_and_head_schedule(graph, sched
     subset_parity(synth_inputs.CONFIGS["C2_resnet18"], 2, fused_tail=True, graph=graph, schedule=schedule)
 
 
+def test_resnet18_size_fifty_rounds_sampled_one_pass_rounds():
+    """k = 1 under the head schedule: Step I, the local step and line 6 in ONE kernel per round."""
+    subset_parity(synth_inputs.CONFIGS["C2_resnet18"], 1, fused_tail=True, schedule=P.SCHED_HEAD)
+
+
 def test_bucketed_tensor_list_sampled_head_schedule_from_graph():
     cfg = synth_inputs.CONFIGS["C5_bucketed"]
     subset_parity(cfg, 2, tensor_numel=bucketed_sizes(cfg), bucket_bytes=cfg["bucket_bytes"], fused_tail=True, graph=True,

@@ -281,6 +281,27 @@ def test_mean_formed_inside_the_first_step_gives_the_same_bits(weights, mu, sigm
     a.close(); b.close()
 
 
+@pytest.mark.parametrize("W,d", [(16, 20_011), (17, 9_001), (40, 6_003), (65, 3_001), (70, 2_500), (131, 1_100), (140, 1_030), (1, 5_000)])
+def test_head_schedule_for_every_worker_count_class(W, d):
+    """The mean-forming first step keeps the tile of all W workers in LDS: one column quad per lane up
+    to 16 workers, two up to 65, one again up to 131 (the LDS budget), and beyond that the mean is
+    formed by a pass of its own.  Every class, k = 1 (mean, step and line 6 in one pass) and k = 2,
+    against the two-stream schedule bit for bit, mean included, and against the oracle."""
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=5e-4, noise_sigma=0.01, seed=79)
+    h, c = synth_inputs.quadratic_data(17, W, d)
+    a = GpuWorkers(W, d, h=h, c=c, **hyper)
+    b = GpuWorkers(W, d, h=h, c=c, **hyper)
+    b.ctx.set_schedule(P.SCHED_HEAD)
+    o = orc.QuadraticOracle(h, c, **hyper)
+    for k, fused_tail in ((1, True), (2, True), (1, False), (2, False), (1, True)):
+        for w in (a, b):
+            w.ctx.round_fused_tail(k) if fused_tail else w.ctx.round(k)
+        o.round(k)
+        assert np.array_equal(a.x(), b.x()) and np.array_equal(a.vel(), b.vel()) and np.array_equal(a.avg(), b.avg()), (k, fused_tail)
+    check_state(b, o, what="head schedule W=%d" % W)
+    a.close(); b.close()
+
+
 def test_packed_tensor_list_is_bit_identical_to_flat_and_matches_oracle():
     W, rounds, k = 4, 3, 2
     sizes = [5, 4096, 1, 3, 8191, 64, 4097, 2, 10000, 7]      # every start alignment, tails of 1..3
