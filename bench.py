@@ -3,16 +3,21 @@
 
 A "step" is one round of Algorithm 1 for all W workers: store the models, start the cross-worker
 mean on the averaging stream, take k local momentum-SGD steps on the compute stream, join, apply
-line 6.  Workload: the ResNet18-sized flat vector (W=16, d=11.2M fp32, momentum 0.9, weight decay
-5e-4, lr 0.05, noise 0.01), all state resident in HBM before timing starts; synthetic data.
+line 6.  Headline workload: the ResNet18-sized flat vector (C2: W=16, d=11.2M fp32, momentum 0.9,
+weight decay 5e-4, lr 0.05, noise 0.01), k = 2, all state resident in HBM before timing starts;
+synthetic data.
 
 Two ways of running the same round are timed:
   separate    cocod_average_begin; cocod_local_steps(k); cocod_average_end_apply
   fused_tail  cocod_average_begin; cocod_local_steps_end_apply(k)   (line 6 inside the last step)
-Prints ONE JSON line.  `value` = worker-param-updates/s = W*d*k / round time at k=2 for the variant
-named in config.variant; the k sweep (both variants, each also replayed from a HIP graph, and under
-the schedule that forms the mean inside the round's first step), the serial schedules, the roofline
-of the step kernels and the CPU oracle timed on the host cores ride along in the same line.
+Prints ONE JSON line.  `value` = worker-param-updates/s = W*d*k / round time for the variant named in
+config.variant under the overlapped two-stream schedule.  The same line carries: the k sweep (both
+variants, each also replayed from a HIP graph, and under the schedule that forms the mean inside the
+round's first step), the serial schedules, what the overlap hides by interval and by cost, the roofline
+of the step kernels, the CPU oracle timed on the host cores, and under "workloads" a compact
+measurement of the other configurations (C3 VGG16-sized, C5 bucketed tensor list with W=64, C4
+MLP-gradient workers).  `--workload X` measures one configuration alone; `--kernels-alone` launches
+every kernel of the round by itself (the program to put under rocprofv3 for per-dispatch counters).
 """
 import argparse
 import json
@@ -25,35 +30,43 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X published dense fp32 matrix rate
 STEP_BYTES = 24                 # plain local step: read x, v, h, c; write x, v (fp32); 16 without momentum
-# HBM bytes per launch of the plain step kernel at this workload from two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999, factors from the known-size copy kernel):
-# profiles/kernels_C2_W16_d11.2M_hbm_counters.md
-STEP_TRAFFIC_BYTES = 4.3038e9
-# the same for the step that carries line 6 (it fetches the mean once per worker at the L2 boundary)
-TAIL_TRAFFIC_BYTES = {1: 5.0400e9, 2: 5.7568e9}     # k = 1 / k >= 2
+# HBM bytes per launch at C2 from two rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999,
+# factors from the known-size copy kernel): profiles/kernels_C2_W16_d11.2M_hbm_counters.md, checked
+# against that file by tests/test_bench_contract.py
+STEP_TRAFFIC_BYTES = 4.3038e9                        # plain step
+TAIL_TRAFFIC_BYTES = {1: 5.0400e9, 2: 5.7568e9}      # step that carries line 6: k = 1 / k >= 2
+
+NAMES = {"C1": "C1_tiny", "C2": "C2_resnet18", "C3": "C3_vgg16", "C4": "C4_mlp", "C5": "C5_bucketed"}
+LABELS = {"C1": "C1 tiny flat vector", "C2": "C2 ResNet18-sized flat vector", "C3": "C3 ImageNet-VGG16-sized flat vector",
+          "C5": "C5 ResNet18-like list of 62 tensors in 25 MiB buckets"}
 
 
-def model_round_bytes(W, d, k):
+def step_bytes(momentum):
+    return STEP_BYTES if momentum else 16
+
+
+def model_round_bytes(W, d, k, per_step=STEP_BYTES):
     """Bytes of one round in the accounting where line 6 is a pass of its own:
     k steps (24) + mean (4(1+1/W)) + line 6 with the mean read once per column (12+4/W)."""
-    return W * d * (STEP_BYTES * k + 16 + 8 / W)
+    return W * d * (per_step * k + 16 + 8 / W)
 
 
-def tail_step_bytes(W, d, k):
+def tail_step_bytes(W, d, k, per_step=STEP_BYTES):
     """Step that carries line 6: the plain step's 24 B plus the stored model (not at k=1, where the
     step reads it anyway) plus the mean, shared by the W workers of a column."""
-    return W * d * (STEP_BYTES + (4 if k > 1 else 0) + 4 / W)
+    return W * d * (per_step + (4 if k > 1 else 0) + 4 / W)
 
 
-def moved_round_bytes(W, d, k, variant):
+def moved_round_bytes(W, d, k, variant, per_step=STEP_BYTES):
     if variant.startswith("head_"):              # no pass for the mean: only its store, and its read by line 6
-        sub = moved_round_bytes(W, d, k, variant[len("head_"):])
-        rides = k >= 2 or (k == 1 and variant.endswith("separate"))    # else the mean is a pass of its own
-        return sub - W * d * 4 if rides else sub
+        if k == 1 and variant.endswith("fused_tail"):
+            return W * d * (per_step + 4 / W)    # one pass: mean, step and line 6 together; the mean is only written
+        return moved_round_bytes(W, d, k, variant[len("head_"):], per_step) - W * d * 4
     if variant in ("separate", "graph_separate"):
-        return model_round_bytes(W, d, k)
-    return W * d * (STEP_BYTES * (k - 1) + 4 * (1 + 1 / W)) + tail_step_bytes(W, d, k)
+        return model_round_bytes(W, d, k, per_step)
+    return W * d * (per_step * (k - 1) + 4 * (1 + 1 / W)) + tail_step_bytes(W, d, k, per_step)
 
 
 def time_rounds(ctx, torch, k, rounds, warmup, variant, want_step_times=True):
@@ -107,7 +120,7 @@ def timelines(ctx, torch, P, k, rounds):
       local_sgd  k steps, then blocking average                         (communicate every k steps, sequential)
       cocod      the round with the mean overlapped and line 6 separate (every k steps, in parallel)
       cocod_fused_tail  the same with line 6 inside the last step
-    Blocking average = a round with zero local steps: every worker lands on the mean of the current models."""
+    Blocking average = cocod_average_apply_fused while idle: every worker lands on the mean of the current models."""
     def timed(body, steps_per_iter):
         for _ in range(2):
             body()
@@ -120,14 +133,9 @@ def timelines(ctx, torch, P, k, rounds):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / rounds / steps_per_iter * 1e3
 
-    def blocking_average():
-        ctx.average_begin()
-        ctx.average_end_apply()
-
     out = {}
-    ctx.set_schedule(P.SCHED_FUSED)       # nothing to overlap with: mean and broadcast in one kernel
-    out["s_sgd"] = timed(lambda: (ctx.local_steps(1), blocking_average()), 1)
-    out["local_sgd"] = timed(lambda: (ctx.local_steps(k), blocking_average()), k)
+    out["s_sgd"] = timed(lambda: (ctx.local_steps(1), ctx.average_apply_fused()), 1)
+    out["local_sgd"] = timed(lambda: (ctx.local_steps(k), ctx.average_apply_fused()), k)
     ctx.set_schedule(P.SCHED_OVERLAP)
     out["cocod"] = timed(lambda: ctx.round(k), k)
     out["cocod_fused_tail"] = timed(lambda: ctx.round_fused_tail(k), k)
@@ -156,11 +164,11 @@ def external_gradient_rounds(ctx, torch, W, d, stride, k, rounds, g32, scratch):
             one_round()
         ctx.sync()
         per_round = (time.perf_counter() - t0) / rounds
-        step_bytes = STEP_BYTES - 8 + gbytes                  # r x, v, g; w x, v
+        per_step = STEP_BYTES - 8 + gbytes                    # r x, v, g; w x, v
         # + the mean's pass, + the mean read by the last step, + the stored model there (at k = 1 the step reads it anyway)
-        moved = W * d * (step_bytes * k + 4 * (1 + 1 / W) + 4 / W + (4 if k > 1 else 0))
+        moved = W * d * (per_step * k + 4 * (1 + 1 / W) + 4 / W + (4 if k > 1 else 0))
         out[name] = {"ms_per_round": per_round * 1e3, "updates_per_s": W * d * k / per_round,
-                     "moved_GBps": moved / per_round / 1e9, "bytes_per_worker_param_step": step_bytes}
+                     "moved_GBps": moved / per_round / 1e9, "bytes_per_worker_param_step": per_step}
     out["k"] = k
     return out
 
@@ -182,6 +190,37 @@ def round_event_times(ctx, torch, stream, k, rounds, variant):
     ctx.sync()
     ms = sorted(marks[r].elapsed_time(marks[r + 1]) for r in range(rounds))
     return {"round_ms_median": ms[len(ms) // 2], "round_ms_min": ms[0]}
+
+
+def overlap_figures(ctx, torch, P, s_avg, k, rounds, step_beside_mean_s):
+    """What running Step I beside Step II buys on one GPU, by cost (the interval figure comes from the
+    kernel trace under profiles/): the plain step alone, the same step while the mean runs on the other
+    stream, and the mean alone.  mean_cost_hidden_frac = 1 - (step beside the mean - step alone) / mean alone:
+    the share of the mean's own duration that does NOT reappear as a slower step."""
+    ctx.set_schedule(P.SCHED_OVERLAP)
+    ctx.local_steps(2)
+    ctx.sync()
+    ctx.step_timing(8)
+    ctx.local_steps(8)                                   # outside a round: nothing runs beside them
+    alone_ms, n = ctx.step_timing_read()[0]
+    ctx.step_timing(0)
+    step_alone_s = alone_ms / n / 1e3
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    mean_ms = []
+    for _ in range(min(rounds, 20) + 2):
+        ctx.sync()
+        a.record(s_avg)
+        ctx.average_begin()                              # the mean starts on the averaging stream at once: compute is idle
+        b.record(s_avg)
+        ctx.average_end_apply()
+        ctx.sync()
+        mean_ms.append(a.elapsed_time(b))
+    mean_alone_s = sorted(mean_ms[2:])[len(mean_ms[2:]) // 2] / 1e3
+    out = {"plain_step_alone_ms": step_alone_s * 1e3, "mean_alone_ms": mean_alone_s * 1e3}
+    if step_beside_mean_s:
+        out["plain_step_beside_mean_ms"] = step_beside_mean_s * 1e3
+        out["mean_cost_hidden_frac"] = 1.0 - (step_beside_mean_s - step_alone_s) / mean_alone_s
+    return out
 
 
 SINGLE_THREAD_SAMPLE = """
@@ -241,17 +280,160 @@ def roofline(name, algorithmic_bytes, seconds, launches, traffic):
             "launches_timed": launches, "algorithmic_bytes_per_launch": algorithmic_bytes}
 
 
-MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X published dense fp32 matrix rate
+class QuadraticWorkload:
+    """Device buffers and context of one of the quadratic-gradient configurations, state resident in HBM."""
+
+    def __init__(self, workload):
+        import torch
+        import paper_1906_12043_amd as P
+        import synth_inputs
+        self.torch, self.P = torch, P
+        self.workload = workload
+        self.cfg = cfg = synth_inputs.CONFIGS[NAMES[workload]]
+        self.W, self.d = cfg["W"], cfg["d"]
+        self.sizes = (synth_inputs.tensor_sizes(cfg["seed"], cfg["n_tensors"], self.d, cfg["tensor_lo"], cfg["tensor_hi"])
+                      if "n_tensors" in cfg else None)
+        dev = torch.device("cuda:0")
+        stride, _, _ = P.plan_layout(self.d, self.sizes, cfg.get("bucket_bytes", 0))
+        self.stride = (stride + 1023) // 1024 * 1024     # worker rows start on 4 KiB boundaries (measured: faster streaming)
+        W = self.W
+        self.xA = torch.zeros((W, self.stride), device=dev)
+        self.xB = torch.zeros((W, self.stride), device=dev)
+        self.v = torch.zeros((W, self.stride), device=dev) if cfg["momentum"] else None
+        self.mean = torch.zeros(self.stride, device=dev)
+        self.h = torch.empty((W, self.stride), device=dev)
+        self.c = torch.empty((W, self.stride), device=dev)
+        self.s_compute, self.s_avg = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+        torch.cuda.synchronize()
+        self.ctx = P.Context(W=W, d=self.d, stride=self.stride, xA=self.xA, xB=self.xB, v=self.v, mean=self.mean, h=self.h,
+                             c=self.c, lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"],
+                             noise_sigma=cfg["noise_sigma"], seed=cfg["seed"], tensor_numel=self.sizes,
+                             bucket_bytes=cfg.get("bucket_bytes", 0), compute_stream=self.s_compute, avg_stream=self.s_avg)
+        self.per_step = step_bytes(cfg["momentum"])
+
+    def copy_rate(self):
+        """What a plain copy of one [W][stride] array reaches on this machine, same launch path (h -> c, before they are filled)."""
+        for timed in (False, True):
+            self.torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20 if timed else 3):
+                self.P.debug_copy(self.s_compute, self.h, self.c, self.W * self.stride)
+            self.ctx.sync()
+            copy_s = (time.perf_counter() - t0) / 20
+        return 8.0 * self.W * self.stride / copy_s / 1e9
+
+    def fill(self):
+        self.ctx.fill_quadratic()
+        self.ctx.sync()
+
+    def close(self):
+        self.ctx.close()
+        del self.xA, self.xB, self.v, self.mean, self.h, self.c
+        self.torch.cuda.empty_cache()
 
 
-def bench_mlp(args):
-    """C4: W=16 perceptron workers 3072-1024-10, batch 128, k=2: rounds/s, and the MFMA roofline of a
+def bench_quadratic(workload, k, variant, steps, warmup, full):
+    """One of C1, C2, C3, C5.  full: also the k sweep, the schedules, the timelines and the caller's-gradient rounds."""
+    import torch
+    import paper_1906_12043_amd as P
+    wl = QuadraticWorkload(workload)
+    cfg, W, d, ctx, per_step = wl.cfg, wl.W, wl.d, wl.ctx, wl.per_step
+    if k not in cfg["k"] and workload != "C2":
+        k = cfg["k"][0]
+    copy_gbps = wl.copy_rate()
+    wl.fill()
+    per_round, plain_s, tail_s, _ = time_rounds(ctx, torch, k, steps, warmup, variant)
+    moved = moved_round_bytes(W, d, k, variant, per_step)
+    out = {
+        "metric": "worker-param-updates/s per CoCoD round (W=%d, d=%.4gM)" % (W, d / 1e6),
+        "value": W * d * k / per_round,
+        "unit": "worker-param-updates/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": per_round * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: W=%d workers x d=%d fp32, quadratic+Philox-noise gradient, momentum %g, wd %g, lr %g"
+                               % (LABELS[workload], W, d, cfg["momentum"], cfg["weight_decay"], cfg["lr"]),
+                   "k": k, "variant": variant,
+                   "schedule": "overlap (2 streams)", "W": W, "d": d},
+        "round_model_GBps": model_round_bytes(W, d, k, per_step) / per_round / 1e9,
+        "round_moved_GBps": moved / per_round / 1e9,
+        "round_moved_frac_of_hbm_peak": moved / per_round / 1e9 / HBM_PEAK_GBS,
+        "copy_kernel_GBps": copy_gbps,          # plain copy of a [W][stride] array on this box, read + write
+        "round_moved_frac_of_copy_kernel": moved / per_round / 1e9 / copy_gbps,
+    }
+    if workload == "C2" and variant == "fused_tail" and k >= 1:
+        # the same round by the hardware counters (bytes across the L2 boundary per launch, from the counter
+        # runs under profiles/): k-1 plain steps, the mean (4(1+1/W) B, ratio 1.000), the step with line 6
+        counted = (k - 1) * STEP_TRAFFIC_BYTES + 4 * (1 + 1 / W) * W * d + TAIL_TRAFFIC_BYTES[min(k, 2)]
+        out["round_counter_GBps"] = counted / per_round / 1e9
+    out.update(round_event_times(ctx, torch, wl.s_compute, k, steps, variant))
+    # "roofline" is the kernel with the largest share of the round's GPU time: with line 6 inside the
+    # last step that is this last step (it moves more bytes than a plain step); the plain step rides
+    # along as "roofline_plain_step" (at k = 2 it always shares the memory system with the mean).
+    plain = tail = None
+    if plain_s:
+        n_plain = steps * (k if variant == "separate" else k - 1)
+        traffic = STEP_TRAFFIC_BYTES if workload == "C2" else None
+        plain = roofline("local_step_kernel<momentum, noise, plain>", per_step * W * d, plain_s, n_plain, traffic)
+    if tail_s:
+        tail_traffic = TAIL_TRAFFIC_BYTES[min(k, 2)] if workload == "C2" else None
+        tail = roofline("local_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k, per_step), tail_s, steps, tail_traffic)
+    if tail and (not plain or tail_s >= plain_s * (k - 1)):
+        out["roofline"] = tail
+        if plain:
+            out["roofline_plain_step"] = plain
+    else:
+        out["roofline"] = plain
+        if tail:
+            out["roofline_line6_step"] = tail
+    if full:
+        prop = torch.cuda.get_device_properties(0)
+        out["device"] = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
+                         "hbm_GiB": prop.total_memory / 2**30, "hip": torch.version.hip}
+        out["overlap"] = overlap_figures(ctx, torch, P, wl.s_avg, k, steps, plain_s if variant == "fused_tail" and k == 2 else None)
+        sweep_rounds = min(steps, 50)
+        variants = {}
+        for name in ("separate", "fused_tail", "graph_separate", "graph_fused_tail", "head_separate", "head_fused_tail",
+                     "head_graph_fused_tail"):
+            sweep = {}
+            for kk in cfg["k"]:
+                pr, ps, ts, hs = time_rounds(ctx, torch, kk, sweep_rounds, 2, name)
+                sweep["k=%d" % kk] = {"ms_per_round": pr * 1e3, "updates_per_s": W * d * kk / pr,
+                                      "model_GBps": model_round_bytes(W, d, kk, per_step) / pr / 1e9,
+                                      "moved_GBps": moved_round_bytes(W, d, kk, name, per_step) / pr / 1e9,
+                                      "plain_step_ms": ps * 1e3 if ps else None,
+                                      "tail_step_ms": ts * 1e3 if ts else None,
+                                      "head_step_ms": hs * 1e3 if hs else None}
+            variants[name] = sweep
+        out["k_sweep"] = variants
+        sched = {}
+        for name, code in (("serial", P.SCHED_SERIAL), ("serial_fused_mean_line6", P.SCHED_FUSED), ("overlap", P.SCHED_OVERLAP)):
+            ctx.set_schedule(code)
+            sched[name] = time_rounds(ctx, torch, k, sweep_rounds, 2, "separate", False)[0] * 1e3
+        out["separate_schedule_ms_per_round"] = sched
+        # line 6 inside the last step, with the mean (a) beside the first k-1 steps on its own stream,
+        # (b) on the compute stream right before the last step, (c) inside the first step
+        sched = {}
+        for name, code in (("overlap", P.SCHED_OVERLAP), ("serial", P.SCHED_SERIAL), ("head", P.SCHED_HEAD)):
+            ctx.set_schedule(code)
+            sched[name] = time_rounds(ctx, torch, k, sweep_rounds, 2, "fused_tail", False)[0] * 1e3
+        ctx.set_schedule(P.SCHED_OVERLAP)
+        out["fused_tail_schedule_ms_per_round"] = sched
+        out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, sweep_rounds)
+        out["external_gradient"] = external_gradient_rounds(ctx, torch, W, d, wl.stride, k, sweep_rounds, wl.h, wl.c)
+    wl.close()
+    return out
+
+
+def bench_mlp(k, variant, steps, warmup, full):
+    """C4: W=16 perceptron workers 3072-1024-10, batch 128: rounds/s, and the MFMA roofline of a
     local step (the two big contractions are 2 * 2*B*in*hid flops per worker-step)."""
     import torch
     import paper_1906_12043_amd as P
     import synth_inputs
     cfg = synth_inputs.CONFIGS["C4_mlp"]
-    W, shape, batch, k = cfg["W"], cfg["mlp"], cfg["batch"], args.k
+    W, shape, batch = cfg["W"], cfg["mlp"], cfg["batch"]
     d = synth_inputs.mlp_param_count(*shape)
     dev = torch.device("cuda:0")
     stride, _, _ = P.plan_layout(d)
@@ -264,52 +446,109 @@ def bench_mlp(args):
     ctx = P.Context(W=W, d=d, stride=stride, xA=xA, xB=xB, v=v, mean=mean, grad=P.GRAD_MLP, mlp=(*shape, batch),
                     lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"],
                     compute_stream=s_compute, avg_stream=s_avg)
-    fused = args.variant == "fused_tail"
-    per_round, plain_s, tail_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, args.variant)
+    fused = variant == "fused_tail"
+    per_round, plain_s, tail_s, _ = time_rounds(ctx, torch, k, steps, warmup, variant)
     # average local step over the round: k-1 plain steps and one that also applies line 6, or k plain ones
     step_s = ((plain_s or 0.0) * (k - 1) + tail_s) / k if fused else plain_s
-    other = "separate" if fused else "fused_tail"
-    other_round = time_rounds(ctx, torch, k, args.steps, args.warmup, other, False)[0]
-    graph_round = time_rounds(ctx, torch, k, args.steps, args.warmup, "graph_" + args.variant)[0]
     n_in, n_hid, n_out = shape
     gemm_flops = W * 2 * (2 * batch * n_in * n_hid)
     all_flops = gemm_flops + W * 3 * (2 * batch * n_hid * n_out)
     achieved = gemm_flops / step_s / 1e12
+    # HBM bytes a local step must move: the parameters and their momentum in and out (the update of every
+    # parameter), the mini-batch written once and read by both contractions' first touch, H and dA once each way
+    step_hbm_bytes = W * (16 * d + 4 * batch * (2 * n_in + 4 * n_hid))
     out = {
         "metric": "worker-param-updates/s per CoCoD round, MLP-gradient workers (W=16, d=3.16M)",
-        "value": W * d * k / per_round, "unit": "worker-param-updates/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": per_round * 1e3, "higher_is_better": True, "scaling": "weak",
+        "value": W * d * k / per_round, "unit": "worker-param-updates/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": per_round * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C4 MLP workers 3072-1024-10, batch 128 fresh N(0,1) inputs per worker-step, momentum 0.9, "
-                               "lr 0.05", "k": k, "W": W, "d": d, "variant": args.variant},
+                               "lr 0.05", "k": k, "W": W, "d": d, "variant": variant, "schedule": "overlap (2 streams)"},
         "local_step_ms": step_s * 1e3,
         "plain_step_ms": plain_s * 1e3 if plain_s else None,
         "line6_step_ms": tail_s * 1e3 if tail_s else None,
-        other + "_ms_per_round": other_round * 1e3,
-        "graph_ms_per_round": graph_round * 1e3,
         "local_step_TFLOPs_all": all_flops / step_s / 1e12,
+        "local_step_hbm_GBps": step_hbm_bytes / step_s / 1e9,
         "roofline": {"bound": "mfma", "kernel": "one local step (5 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
                      "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": step_s * 1e3,
-                     "launches_timed": args.steps * k, "algorithmic_flops_per_launch": gemm_flops},
+                     "launches_timed": steps * k, "algorithmic_flops_per_launch": gemm_flops},
     }
+    if full:
+        other = "separate" if fused else "fused_tail"
+        out[other + "_ms_per_round"] = time_rounds(ctx, torch, k, steps, warmup, other, False)[0] * 1e3
+        out["graph_ms_per_round"] = time_rounds(ctx, torch, k, steps, warmup, "graph_" + variant)[0] * 1e3
     ctx.close()
-    print(json.dumps(out))
+    del xA, xB, v, mean
+    torch.cuda.empty_cache()
+    return out
+
+
+def compact(line):
+    """The part of a workload's line that rides along in the default run."""
+    keep = ("metric", "value", "unit", "ms_per_step", "steps", "warmup", "dtype", "config", "roofline", "roofline_plain_step",
+            "round_moved_GBps", "round_moved_frac_of_hbm_peak", "local_step_ms", "local_step_hbm_GBps")
+    return {key: line[key] for key in keep if key in line}
+
+
+def kernels_alone(reps=5):
+    """Launch each kernel of the round a few times, alone, at the benchmark shape (C2: W=16, d=11.2M), plus a
+    plain copy of known size -- the program to put under rocprofv3 for per-dispatch hardware counters:
+
+        rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -- python3 bench.py --kernels-alone
+        rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT -- python3 bench.py --kernels-alone
+
+    The copy moves exactly 4*W*stride bytes in and 4*W*stride bytes out per launch; the ratio of its counter
+    reading to that figure is the scale factor applied to the other kernels' readings."""
+    import paper_1906_12043_amd as P
+    wl = QuadraticWorkload("C2")
+    ctx = wl.ctx
+    ctx.set_schedule(P.SCHED_SERIAL)            # one stream: every kernel runs by itself
+    for _ in range(reps):                       # copy: 4*W*stride bytes each way
+        P.debug_copy(wl.s_compute, wl.h, wl.xB, wl.W * wl.stride)
+    ctx.sync()
+    wl.fill()
+    ctx.local_steps(reps)                       # plain step, in place
+    ctx.sync()
+    for _ in range(reps):                       # mean, plain step (out of place), line 6 back to back
+        ctx.round(1)
+    ctx.sync()
+    for _ in range(reps):                       # mean + line 6 in one kernel
+        ctx.local_steps(1)
+        ctx.average_apply_fused()
+    ctx.sync()
+    for _ in range(reps):                       # line 6 inside the last step: mean, plain step, step with line 6
+        ctx.round_fused_tail(2)
+    ctx.sync()
+    for _ in range(reps):                       # k = 1: the step with line 6 reads the stored models as its input
+        ctx.round_fused_tail(1)
+    ctx.sync()
+    ctx.set_schedule(P.SCHED_HEAD)              # the mean formed inside the round's first step
+    for _ in range(reps):
+        ctx.round_fused_tail(2)
+    ctx.sync()
+    for _ in range(reps):                       # k = 1: mean, step and line 6 in one kernel
+        ctx.round_fused_tail(1)
+    ctx.sync()
+    print("kernels alone: done, W=%d d=%d stride=%d reps=%d" % (wl.W, wl.d, wl.stride, reps))
+    wl.close()
     return 0
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", choices=("C1", "C2", "C3", "C4", "C5"), default="C2",
-                    help="C2: the headline workload (ResNet18-sized, W=16); C1 tiny, C3 VGG16-sized, C5 bucketed "
-                         "tensor list with W=64 (same quadratic path); C4: the MLP-gradient workers")
+    ap.add_argument("--workload", choices=("C1", "C2", "C3", "C4", "C5"), default=None,
+                    help="measure one configuration alone.  Default: the headline workload C2 (ResNet18-sized, W=16) in "
+                         "full, with compact measurements of C3 (VGG16-sized), C5 (bucketed tensor list, W=64) and C4 "
+                         "(MLP-gradient workers) under \"workloads\"")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50, help="timed rounds")
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100, help="timed rounds")
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--k", type=int, default=2, help="local steps per round for the headline value")
     ap.add_argument("--variant", choices=("separate", "fused_tail"), default="fused_tail")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--headline-only", action="store_true", help="skip the other variant, the k sweep and the serial schedules")
+    ap.add_argument("--headline-only", action="store_true", help="skip the k sweep, the schedules and the other workloads")
+    ap.add_argument("--kernels-alone", action="store_true", help="launch every kernel of the C2 round by itself (for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the W workers are replicas in one MI355X's HBM); "
@@ -325,132 +564,28 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.kernels_alone:
+        return kernels_alone()
+    full = not args.headline_only
     if args.workload == "C4":
-        return bench_mlp(args)
+        print(json.dumps(bench_mlp(args.k, args.variant, args.steps, args.warmup, full)))
+        return 0
+    if args.workload is not None:
+        out = bench_quadratic(args.workload, args.k, args.variant, args.steps, args.warmup, full)
+        if not args.no_cpu_baseline and args.workload == "C2":
+            out["cpu_baseline"] = cpu_baseline(synth_inputs.CONFIGS[NAMES["C2"]], args.k)
+        print(json.dumps(out))
+        return 0
 
-    names = {"C1": "C1_tiny", "C2": "C2_resnet18", "C3": "C3_vgg16", "C5": "C5_bucketed"}
-    labels = {"C1": "C1 tiny flat vector", "C2": "C2 ResNet18-sized flat vector", "C3": "C3 ImageNet-VGG16-sized flat vector",
-              "C5": "C5 ResNet18-like list of 62 tensors in 25 MiB buckets"}
-    cfg = synth_inputs.CONFIGS[names[args.workload]]
-    W, d = cfg["W"], cfg["d"]
-    sizes = (synth_inputs.tensor_sizes(cfg["seed"], cfg["n_tensors"], d, cfg["tensor_lo"], cfg["tensor_hi"])
-             if "n_tensors" in cfg else None)
-    if args.k not in cfg["k"] and args.workload != "C2":
-        args.k = cfg["k"][0]
-    dev = torch.device("cuda:0")
-    stride, _, _ = P.plan_layout(d, sizes, cfg.get("bucket_bytes", 0))
-    stride = (stride + 1023) // 1024 * 1024     # worker rows start on 4 KiB boundaries (measured: faster streaming)
-    xA = torch.zeros((W, stride), device=dev)
-    xB = torch.zeros((W, stride), device=dev)
-    v = torch.zeros((W, stride), device=dev) if cfg["momentum"] else None
-    mean = torch.zeros(stride, device=dev)
-    h = torch.empty((W, stride), device=dev)
-    c = torch.empty((W, stride), device=dev)
-    s_compute, s_avg = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
-    torch.cuda.synchronize()
-    ctx = P.Context(W=W, d=d, stride=stride, xA=xA, xB=xB, v=v, mean=mean, h=h, c=c, lr=cfg["lr"],
-                    momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], noise_sigma=cfg["noise_sigma"],
-                    seed=cfg["seed"], tensor_numel=sizes, bucket_bytes=cfg.get("bucket_bytes", 0),
-                    compute_stream=s_compute, avg_stream=s_avg)
-    # what a plain copy of one [W][stride] array reaches on this machine, same launch path (h -> c, before they are filled)
-    for timed in (False, True):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(20 if timed else 3):
-            P.debug_copy(s_compute, h, c, W * stride)
-        ctx.sync()
-        copy_s = (time.perf_counter() - t0) / 20
-    copy_gbps = 8.0 * W * stride / copy_s / 1e9
-    ctx.fill_quadratic()
-    ctx.sync()
-
-    global STEP_BYTES
-    if not cfg["momentum"]:
-        STEP_BYTES = 16
-    traffic = STEP_TRAFFIC_BYTES if args.workload == "C2" else None
-    k, variant = args.k, args.variant
-    per_round, plain_s, tail_s, _ = time_rounds(ctx, torch, k, args.steps, args.warmup, variant)
-    out = {
-        "metric": "worker-param-updates/s per CoCoD round (W=%d, d=%.4gM)" % (W, d / 1e6),
-        "value": W * d * k / per_round,
-        "unit": "worker-param-updates/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": per_round * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: W=%d workers x d=%d fp32, quadratic+Philox-noise gradient, momentum %g, wd %g, lr %g"
-                               % (labels[args.workload], W, d, cfg["momentum"], cfg["weight_decay"], cfg["lr"]),
-                   "k": k, "variant": variant,
-                   "schedule": "overlap (2 streams)", "W": W, "d": d},
-        "round_model_GBps": model_round_bytes(W, d, k) / per_round / 1e9,
-        "round_moved_GBps": moved_round_bytes(W, d, k, variant) / per_round / 1e9,
-        "round_moved_frac_of_hbm_peak": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / HBM_PEAK_GBS,
-        "copy_kernel_GBps": copy_gbps,          # plain copy of a [W][stride] array on this machine, read + write
-        "round_moved_frac_of_copy_kernel": moved_round_bytes(W, d, k, variant) / per_round / 1e9 / copy_gbps,
-    }
-    if args.workload == "C2" and variant == "fused_tail" and k >= 1:
-        # the same round by the hardware counters (bytes across the L2 boundary per launch, from the counter
-        # runs under profiles/): k-1 plain steps, the mean (4(1+1/W) B, ratio 1.000), the step with line 6
-        counted = (k - 1) * STEP_TRAFFIC_BYTES + 4 * (1 + 1 / W) * W * d + TAIL_TRAFFIC_BYTES[min(k, 2)]
-        out["round_counter_GBps"] = counted / per_round / 1e9
-    out.update(round_event_times(ctx, torch, s_compute, k, args.steps, variant))
-    prop = torch.cuda.get_device_properties(0)
-    out["device"] = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
-                     "hbm_GiB": prop.total_memory / 2**30, "hip": torch.version.hip}
-    # "roofline" is the kernel with the largest share of the round's GPU time: with line 6 inside the
-    # last step that is this last step (it moves more bytes than a plain step); the plain step rides
-    # along as "roofline_plain_step" (at k = 2 it always shares the memory system with the mean).
-    plain = tail = None
-    if plain_s:
-        n_plain = args.steps * (k if variant == "separate" else k - 1)
-        plain = roofline("quad_step_kernel<momentum, noise, plain>", STEP_BYTES * W * d, plain_s, n_plain, traffic)
-    if tail_s:
-        tail_traffic = TAIL_TRAFFIC_BYTES[min(k, 2)] if args.workload == "C2" else None
-        tail = roofline("quad_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k), tail_s, args.steps, tail_traffic)
-    if tail and (not plain or tail_s >= plain_s * (k - 1)):
-        out["roofline"] = tail
-        if plain:
-            out["roofline_plain_step"] = plain
-    else:
-        out["roofline"] = plain
-        if tail:
-            out["roofline_line6_step"] = tail
-    if not args.headline_only:
-        variants = {}
-        for name in ("separate", "fused_tail", "graph_separate", "graph_fused_tail", "head_separate", "head_fused_tail",
-                     "head_graph_fused_tail"):
-            sweep = {}
-            for kk in cfg["k"]:
-                pr, ps, ts, hs = time_rounds(ctx, torch, kk, args.steps, 2, name)
-                sweep["k=%d" % kk] = {"ms_per_round": pr * 1e3, "updates_per_s": W * d * kk / pr,
-                                      "model_GBps": model_round_bytes(W, d, kk) / pr / 1e9,
-                                      "moved_GBps": moved_round_bytes(W, d, kk, name) / pr / 1e9,
-                                      "plain_step_ms": ps * 1e3 if ps else None,
-                                      "tail_step_ms": ts * 1e3 if ts else None,
-                                      "head_step_ms": hs * 1e3 if hs else None}
-            variants[name] = sweep
-        out["k_sweep"] = variants
-        sched = {}
-        for name, code in (("serial", P.SCHED_SERIAL), ("serial_fused_mean_line6", P.SCHED_FUSED), ("overlap", P.SCHED_OVERLAP)):
-            ctx.set_schedule(code)
-            pr = time_rounds(ctx, torch, k, args.steps, 2, "separate", False)[0]
-            sched[name] = pr * 1e3
-        out["separate_schedule_ms_per_round"] = sched
-        # line 6 inside the last step, with the mean (a) beside the first k-1 steps on its own stream,
-        # (b) on the compute stream right before the last step, (c) inside the first step
-        sched = {}
-        for name, code in (("overlap", P.SCHED_OVERLAP), ("serial", P.SCHED_SERIAL), ("head", P.SCHED_HEAD)):
-            ctx.set_schedule(code)
-            sched[name] = time_rounds(ctx, torch, k, args.steps, 2, "fused_tail", False)[0] * 1e3
-        ctx.set_schedule(P.SCHED_OVERLAP)
-        out["fused_tail_schedule_ms_per_round"] = sched
-        out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, args.steps)
-        out["external_gradient"] = external_gradient_rounds(ctx, torch, W, d, stride, k, args.steps, h, c)
-    ctx.close()
-    del xA, xB, v, mean, h, c
-    torch.cuda.empty_cache()
-    if not args.no_cpu_baseline and args.workload == "C2":
-        out["cpu_baseline"] = cpu_baseline(cfg, k)
+    out = bench_quadratic("C2", args.k, args.variant, args.steps, args.warmup, full)
+    if full:                                    # the other configurations, a few timed rounds each
+        others = {}
+        others["C3"] = compact(bench_quadratic("C3", 2, args.variant, 10, 3, False))
+        others["C5"] = compact(bench_quadratic("C5", 2, args.variant, 20, 3, False))
+        others["C4"] = compact(bench_mlp(2, args.variant, 30, 5, False))
+        out["workloads"] = others
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(synth_inputs.CONFIGS[NAMES["C2"]], args.k)
     print(json.dumps(out))
     return 0
 

@@ -65,6 +65,9 @@ __global__ __launch_bounds__(kAvgThreads) void wmean_kernel(const float *snap, u
                                                             uint64_t begin, uint64_t n_quads,
                                                             const float *weights, float *mean)
 {
+#ifdef COCOD_AVG_PRIO
+    __builtin_amdgcn_s_setprio(COCOD_AVG_PRIO);
+#endif
     const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
     if (quad >= n_quads) return;
     const uint64_t e = begin + quad * 4;

@@ -24,5 +24,7 @@ def test_byte_accounting_of_the_round():
     assert bench.moved_round_bytes(W, d, 4, "graph_fused_tail") == wp * (96 + 8 + 0.5)
     # the mean formed inside the first step: no pass over the stored models for it
     assert bench.moved_round_bytes(W, d, 2, "head_fused_tail") == wp * (48 + 4 + 0.5)
-    assert bench.moved_round_bytes(W, d, 1, "head_fused_tail") == bench.moved_round_bytes(W, d, 1, "fused_tail")
+    # k = 1 under that schedule: mean, step and line 6 in one pass, the mean only written
+    assert bench.moved_round_bytes(W, d, 1, "head_fused_tail") == wp * 24.25
+    assert bench.moved_round_bytes(W, d, 1, "head_separate") == wp * (24 + 12.25 + 0.25)
     assert bench.tail_step_bytes(W, d, 2) == wp * 28.25 and bench.tail_step_bytes(W, d, 1) == wp * 24.25
