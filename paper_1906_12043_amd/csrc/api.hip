@@ -109,11 +109,17 @@ int hip_fail(cocod_ctx *ctx, hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);         \
     } while (0)
 
+// Block order of a line-6 step whose mean exceeds the cache: panels of this many tiles (4 MiB of the mean;
+// every worker streams 4 MiB of each of its arrays per panel).  Measured at W = 16, d = 138 M: 9.9 ms per
+// launch, against 10.6 ms with the worker fastest for every single tile and 11.4 ms on the (tiles, workers)
+// grid, where the mean comes from memory once per worker.
+constexpr uint32_t kPanelTiles = 16384;
+
 // A mean vector up to this size is expected to stay in the 256 MB last-level cache while the W
 // workers of a line-6 step read it one after the other.
 constexpr uint64_t kMeanCacheBytes = 128ull << 20;
-// one grid dimension holds fewer than 2^32 threads: with 256-thread blocks, fewer than 2^24 blocks
-constexpr uint64_t kMaxBlocksPerGridDim = 1ull << 24;
+// one grid dimension holds fewer than 2^32 threads
+constexpr uint64_t kMaxThreadsPerGridDim = 1ull << 32;
 // the mean-forming steps launch up to four 1024-thread blocks per chunk in one grid dimension
 constexpr uint64_t kMaxChunksMeanStep = 1ull << 20;
 
@@ -330,11 +336,11 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         }
         global += ctx->tensor_numel[t];
     }
-    // Launch limits.  A grid dimension holds fewer than 2^32 THREADS, i.e. fewer than 2^24 blocks of 256: the
-    // (chunks, workers) grid of the step kernel needs chunks < 2^24 (implied by d < 2^34) and W <= 65535 (checked
-    // above).  The 1-D worker-fastest grid of the line-6 step puts chunks * W blocks into ONE dimension and is
-    // only used below that limit (see enqueue_step).  The total is capped as well, so that block counts stay
-    // inside 32-bit arithmetic everywhere.
+    // Launch limits.  A grid dimension holds fewer than 2^32 THREADS.  The (tiles, workers) grid of the local
+    // step has up to four single-wave blocks per chunk in x (chunks < 2^24 is implied by d < 2^34) and W <= 65535
+    // in y (checked above); the orders that put more into ONE dimension (panels of a line-6 step, 1024-thread
+    // blocks of the mean-forming steps) are only used below that limit (see enqueue_step).  The total is capped
+    // as well, so that block counts stay inside 32-bit arithmetic everywhere.
     if (ctx->chunks.size() * static_cast<uint64_t>(cfg->W) > 0x7fffffffull) {
         delete ctx;
         return fail(nullptr, COCOD_ERR_INVALID, "W * d is too large for one launch (more than 2^31 chunks of 1024 elements)");
@@ -474,9 +480,10 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
         p.step_base = ctx->capturing ? ctx->d_step : nullptr;
-        // worker-fastest order: 4 * chunks * W single-wave blocks in one grid dimension, which holds < 2^32 threads
-        p.worker_fastest = ctx->padded_d * sizeof(float) > kMeanCacheBytes &&
-                           ctx->chunks.size() * static_cast<uint64_t>(ctx->cfg.W) < kMaxBlocksPerGridDim ? 1u : 0u;
+        // (4 * chunks * W single-wave blocks plus the padding of the last panel in one grid dimension)
+        p.panel_tiles = ctx->padded_d * sizeof(float) > kMeanCacheBytes &&
+                        (4 * ctx->chunks.size() + kPanelTiles) * static_cast<uint64_t>(ctx->cfg.W) * 64 < kMaxThreadsPerGridDim
+                            ? kPanelTiles : 0u;
         // Step I inside the round's first step: that step reads exactly the stored models (when there are
         // too many workers for its LDS tile, the mean stays pending and is formed just before line 6)
         const bool head = ctx->schedule == COCOD_SCHED_HEAD && ctx->mean_pending && ctx->store_pending && !g_ext &&

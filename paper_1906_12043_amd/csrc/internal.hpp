@@ -39,7 +39,8 @@ struct StepParams {
     uint32_t key0, key1; // generator key (seed low, seed high)
     uint32_t step;       // global step counter t (relative to *step_base when that is set)
     const uint32_t *step_base;   // non-null inside a replayable graph: device word holding t at the start of the replay
-    uint32_t worker_fastest;   // line-6 step only: order blocks worker-fastest (mean larger than the cache)
+    uint32_t panel_tiles;      // line-6 step only, non-zero: blocks run in panels of this many tiles, worker by worker
+                               // inside a panel (for a mean larger than the cache); 0 = grid (tiles, workers)
     float *mean_out;           // non-null: first step of a round that also forms the mean of the models it reads
     const float *weights;      //           (Step I inside Step II's first pass); p_i, nullptr = 1/W
 };

@@ -86,12 +86,22 @@ __global__ __launch_bounds__(64 * NWMAX) void local_step_kernel(const StepParams
     extern __shared__ __attribute__((aligned(16))) float lds[];
 
     // Grid: x = tiles, y = worker groups.  A step with line 6 whose mean does not fit the last-level
-    // cache runs on a 1-D grid with the worker group fastest instead, so that the blocks which read
-    // the same piece of the mean run together and it comes from memory once.
-    const bool group_fastest = !FORMS_MEAN && LINE6 && p.worker_fastest;
-    const uint32_t n_groups = group_fastest ? (p.W + (blockDim.x >> 6) - 1) / (blockDim.x >> 6) : 1u;
-    const uint32_t tile_id = group_fastest ? blockIdx.x / n_groups : blockIdx.x;
-    const uint32_t group = group_fastest ? blockIdx.x % n_groups : blockIdx.y;
+    // cache runs on a 1-D grid in PANELS of p.panel_tiles tiles instead: inside a panel the blocks
+    // go worker by worker, so every worker still streams a contiguous run of its row, and the W readers
+    // of a panel of the mean run close enough together for it to come from memory once.
+    const uint32_t panel_tiles = (!FORMS_MEAN && LINE6) ? p.panel_tiles : 0u;
+    uint32_t tile_id = blockIdx.x, group = blockIdx.y;
+    if (panel_tiles != 0) {
+        const uint32_t n_groups = (p.W + (blockDim.x >> 6) - 1) / (blockDim.x >> 6);
+        const uint32_t n_tiles = p.n_chunks * PARTS;
+        const uint32_t per_panel = panel_tiles * n_groups;
+        const uint32_t panel = blockIdx.x / per_panel, r = blockIdx.x % per_panel;
+        const uint32_t first_tile = panel * panel_tiles;
+        const uint32_t here = n_tiles - first_tile < panel_tiles ? n_tiles - first_tile : panel_tiles;   // the last panel is short
+        group = r / here;
+        tile_id = first_tile + r % here;
+        if (group >= n_groups) return;                       // block-uniform: padding of the short last panel
+    }
     const uint32_t chunk_id = tile_id / PARTS, part = tile_id % PARTS;
     const Chunk ck = p.table[chunk_id];
     const uint32_t first = part * TILE_ELEMS;                 // first element of the tile inside its chunk
@@ -264,7 +274,9 @@ hipError_t launch_one(hipStream_t stream, const StepParams &p, uint32_t waves, h
     constexpr bool LINE6 = MODE == kModeTail || MODE == kModeTailIn;
     const uint32_t groups = FORMS_MEAN ? 1u : (p.W + waves - 1) / waves;
     const uint32_t tiles = p.n_chunks * (4 / Q);
-    const dim3 grid = (LINE6 && p.worker_fastest) ? dim3(tiles * groups) : dim3(tiles, groups), block(64 * waves);
+    // panels: every panel takes panel_tiles * groups block ids, the short last one included
+    const uint32_t panels = p.panel_tiles ? (tiles + p.panel_tiles - 1) / p.panel_tiles : 0;
+    const dim3 grid = (LINE6 && p.panel_tiles) ? dim3(panels * p.panel_tiles * groups) : dim3(tiles, groups), block(64 * waves);
     if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, start, stop, 0, p);
     else               hipLaunchKernelGGL(kernel, grid, block, lds, stream, p);
     return hipGetLastError();

@@ -129,9 +129,11 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     //   forward : A = X [batch][n_in], K-contiguous: a quad is 4 consecutive k of one row m
     //   backward: A = X^T, read from X M-contiguous: a quad is 4 consecutive rows m of one sample k
     //   B tile  : kBK x BN, N-contiguous (W1 rows, or dA rows)
-    constexpr int A_QUADS = BM * kBK / 4, PA = A_QUADS / THREADS;
+    // (a tile with fewer A quads than threads is staged by the block's first A_QUADS threads: whole waves)
+    constexpr int A_QUADS = BM * kBK / 4, PA = A_QUADS >= THREADS ? A_QUADS / THREADS : 1;
     constexpr int B_QUADS = kBK * BN / 4, PB = B_QUADS / THREADS;
-    static_assert(PA * THREADS == A_QUADS && PB * THREADS == B_QUADS, "tile must split evenly over the block");
+    constexpr bool A_ALL = A_QUADS >= THREADS;
+    static_assert((A_ALL ? PA * THREADS == A_QUADS : A_QUADS % 64 == 0) && PB * THREADS == B_QUADS, "tile must split evenly over the block");
     static_assert(EPI != kFwd || (PA <= 2 && PB <= 4), "the forward loop spreads the staging traffic over fixed slots of the MFMA chain");
     constexpr int A_MINOR = (EPI == kFwd) ? kBK / 4 : BM / 4;   // quads along the contiguous direction
     constexpr int A_MAJOR_PER_PASS = THREADS / A_MINOR;
@@ -163,21 +165,25 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
     f4 ra[NSETS][PA], rb[NSETS][PB];
     auto load_slice = [&](auto set, uint32_t slice) {
         constexpr int S = decltype(set)::value;
-        #pragma unroll
-        for (int i = 0; i < PA; ++i) ra[S][i] = *reinterpret_cast<const f4 *>(a_src + slice * a_slice + i * a_pass);
+        if (A_ALL || t < A_QUADS) {
+            #pragma unroll
+            for (int i = 0; i < PA; ++i) ra[S][i] = *reinterpret_cast<const f4 *>(a_src + slice * a_slice + i * a_pass);
+        }
         #pragma unroll
         for (int i = 0; i < PB; ++i)
             rb[S][i] = *reinterpret_cast<const f4 *>(b_src + (static_cast<uint64_t>(slice) * kBK + static_cast<uint64_t>(i) * B_K_PER_PASS) * ldb);
     };
     auto stage_to_lds = [&](auto set, uint32_t buf) {
         constexpr int S = decltype(set)::value;
-        #pragma unroll
-        for (int i = 0; i < PA; ++i) {
-            const uint32_t major = a_major + i * A_MAJOR_PER_PASS;
+        if (A_ALL || t < A_QUADS) {
             #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (EPI == kFwd) As[buf][major][a_minor + j] = ra[S][i][j];      // (row, k)
-                else             As[buf][a_minor + j][major] = ra[S][i][j];      // transposed on the way in
+            for (int i = 0; i < PA; ++i) {
+                const uint32_t major = a_major + i * A_MAJOR_PER_PASS;
+                #pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (EPI == kFwd) As[buf][major][a_minor + j] = ra[S][i][j];      // (row, k)
+                    else             As[buf][a_minor + j][major] = ra[S][i][j];      // transposed on the way in
+                }
             }
         }
         #pragma unroll
@@ -590,8 +596,12 @@ hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
     if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
     const hipError_t head_rc = launch_heads(stream, p, std::make_integer_sequence<int, kMaxOut>{});
     if (head_rc != hipSuccess) return head_rc;
-    if (p.snap) { if (wide) launch_gemm<kBwdTail, 2, 4>(stream, p); else launch_gemm<kBwdTail, 2, 2>(stream, p); }
-    else        { if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p); }
+#ifndef BWD_NWM
+#define BWD_NWM 2
+#define BWD_NWN 4
+#endif
+    if (p.snap) { if (wide) launch_gemm<kBwdTail, BWD_NWM, BWD_NWN>(stream, p); else launch_gemm<kBwdTail, 2, 2>(stream, p); }
+    else        { if (wide) launch_gemm<kBwd, BWD_NWM, BWD_NWN>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p); }
     return hipGetLastError();
 }
 
