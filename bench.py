@@ -35,8 +35,8 @@ STEP_BYTES = 24                 # plain local step: read x, v, h, c; write x, v 
 # HBM bytes per launch at C2 from two rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 0.999,
 # factors from the known-size copy kernel): profiles/kernels_C2_W16_d11.2M_hbm_counters.md, checked
 # against that file by tests/test_bench_contract.py
-STEP_TRAFFIC_BYTES = 4.3038e9                        # plain step
-TAIL_TRAFFIC_BYTES = {1: 5.0400e9, 2: 5.7568e9}      # step that carries line 6: k = 1 / k >= 2
+STEP_TRAFFIC_BYTES = 4.3034e9                        # plain step
+TAIL_TRAFFIC_BYTES = {1: 5.0620e9, 2: 5.7788e9}      # step that carries line 6: k = 1 / k >= 2
 
 NAMES = {"C1": "C1_tiny", "C2": "C2_resnet18", "C3": "C3_vgg16", "C4": "C4_mlp", "C5": "C5_bucketed"}
 LABELS = {"C1": "C1 tiny flat vector", "C2": "C2 ResNet18-sized flat vector", "C3": "C3 ImageNet-VGG16-sized flat vector",
@@ -368,25 +368,31 @@ def bench_quadratic(workload, k, variant, steps, warmup, full):
         counted = (k - 1) * STEP_TRAFFIC_BYTES + 4 * (1 + 1 / W) * W * d + TAIL_TRAFFIC_BYTES[min(k, 2)]
         out["round_counter_GBps"] = counted / per_round / 1e9
     out.update(round_event_times(ctx, torch, wl.s_compute, k, steps, variant))
-    # "roofline" is the kernel with the largest share of the round's GPU time: with line 6 inside the
-    # last step that is this last step (it moves more bytes than a plain step); the plain step rides
-    # along as "roofline_plain_step" (at k = 2 it always shares the memory system with the mean).
+    # "roofline" is the step that carries line 6 when the round has one: it moves the most bytes per launch
+    # and has the memory system to itself.  The plain step rides along; as the FIRST step of a round it shares
+    # HBM with the mean on the other stream and runs about as long, so its own bytes over its duration
+    # understate what the memory system moves then: "roofline_first_step_and_mean" counts both kernels' bytes
+    # over the step's duration (the mean lies inside it: profiles/round_C2_...md).
     plain = tail = None
     if plain_s:
         n_plain = steps * (k if variant == "separate" else k - 1)
         traffic = STEP_TRAFFIC_BYTES if workload == "C2" else None
         plain = roofline("local_step_kernel<momentum, noise, plain>", per_step * W * d, plain_s, n_plain, traffic)
+        if k <= 2:
+            plain["shares_hbm_with"] = "wmean_kernel on the averaging stream (every timed launch is a round's first step)"
     if tail_s:
         tail_traffic = TAIL_TRAFFIC_BYTES[min(k, 2)] if workload == "C2" else None
         tail = roofline("local_step_kernel<momentum, noise, line 6>", tail_step_bytes(W, d, k, per_step), tail_s, steps, tail_traffic)
-    if tail and (not plain or tail_s >= plain_s * (k - 1)):
+    if tail:
         out["roofline"] = tail
         if plain:
             out["roofline_plain_step"] = plain
+            if k == 2:
+                both = per_step * W * d + 4 * (1 + 1 / W) * W * d
+                out["roofline_first_step_and_mean"] = roofline("local_step_kernel<plain> + wmean_kernel running beside it", both,
+                                                               plain_s, steps, None)
     else:
         out["roofline"] = plain
-        if tail:
-            out["roofline_line6_step"] = tail
     if full:
         prop = torch.cuda.get_device_properties(0)
         out["device"] = {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
