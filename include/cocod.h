@@ -68,9 +68,10 @@ typedef enum cocod_schedule {
     COCOD_SCHED_FUSED = 2,     /* mean and line 6 in one kernel after the local steps */
     COCOD_SCHED_HEAD = 3       /* mean formed inside the first local step of the round, which reads every
                                   stored model anyway: Step I costs one 4/W-byte store per parameter and no
-                                  pass of its own (built-in quadratic gradient; whenever the round's first
-                                  step is not such a step, the mean is formed on compute_stream just before
-                                  line 6 needs it) */
+                                  pass of its own; with k = 1 through cocod_local_steps_end_apply the mean,
+                                  the step and line 6 are ONE kernel (built-in quadratic gradient, W <= 131
+                                  workers, d < 2^30; whenever the round's first step is not such a step, the
+                                  mean is formed on compute_stream just before line 6 needs it) */
 } cocod_schedule;
 
 enum {

@@ -39,7 +39,7 @@ enum { kGradQuadNoisy = 0, kGradQuadExact = 1, kGradExternal = 2, kGradExternalB
 // ONE definition for every kernel that takes a step, with every fused multiply-add written out and
 // contraction switched off: left to the compiler, which products get fused depends on the code around
 // them (h (x - c) + sigma z can become fma(sigma, z, .) or fma(h, x - c, .)), and kernels that must
-// agree bit for bit (row-per-block, column-walking, worker-tile) would differ in the last place.
+// agree bit for bit (every mode and launch shape of the step) would differ in the last place.
 template <bool HAS_V, bool QUADRATIC, bool NOISY, bool LINE6>
 __device__ __forceinline__ void local_step_quad(f4 &x, f4 &v, const f4 x0, const f4 v0, const f4 a, const f4 c, const f4 z,
                                                 float sigma, float lr, float momentum, float weight_decay,
