@@ -39,6 +39,8 @@ def same_bits(a, b, what):
     (False, False, True, P.SCHED_OVERLAP),
     (True, True, True, P.SCHED_SERIAL),
     (False, True, False, P.SCHED_FUSED),
+    (True, True, True, P.SCHED_HEAD),            # mean-forming first step, and k = 1 as ONE kernel, inside a graph
+    (False, False, False, P.SCHED_HEAD),
 ])
 def test_graph_rounds_match_eager_rounds_bit_for_bit(packed, two_streams, fused_tail, schedule):
     W, k, rounds = 5, 2, 9
