@@ -153,7 +153,7 @@ def test_line6_preserves_worker_mean_and_first_round_is_identity():
 
 
 def test_optimizer_lines_match_a_library_optimizer():
-    """The momentum / weight-decay update of local_steps (reading R1 of the experiments' optimizer:
+    """The momentum / weight-decay update of local_steps (the experiments' optimizer as read here:
     g = G + wd x; v = mu v + g; x = x - lr v, v0 = 0, no dampening) against torch.optim.SGD driving the
     same network through autograd, three steps, W = 2 workers with their own mini-batches.  Values of
     lr, mu, wd are all different so that a swapped or misplaced factor shows."""
@@ -211,7 +211,7 @@ def test_optimizer_lines_hand_values():
 
 
 def test_fp32_evaluations_of_the_benchmark_mlp_drift_apart():
-    """Reading R19's evidence.  At the benchmark's shape and hyper-parameters (3072-1024-10, batch 128,
+    """Evidence for how free-running parity of this workload is bounded.  At the benchmark's shape and hyper-parameters (3072-1024-10, batch 128,
     lr 0.05, momentum 0.9) the iteration amplifies rounding differences: a copy of the oracle whose
     STATE alone is rounded to fp32 after every update (arithmetic still fp64) and a copy that does all
     arithmetic in fp32 both leave the fp64 run at a geometric rate.  Early rounds agree to fp32
