@@ -596,12 +596,8 @@ hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
     if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
     const hipError_t head_rc = launch_heads(stream, p, std::make_integer_sequence<int, kMaxOut>{});
     if (head_rc != hipSuccess) return head_rc;
-#ifndef BWD_NWM
-#define BWD_NWM 2
-#define BWD_NWN 4
-#endif
-    if (p.snap) { if (wide) launch_gemm<kBwdTail, BWD_NWM, BWD_NWN>(stream, p); else launch_gemm<kBwdTail, 2, 2>(stream, p); }
-    else        { if (wide) launch_gemm<kBwd, BWD_NWM, BWD_NWN>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p); }
+    if (p.snap) { if (wide) launch_gemm<kBwdTail, 2, 4>(stream, p); else launch_gemm<kBwdTail, 2, 2>(stream, p); }
+    else        { if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p); }
     return hipGetLastError();
 }
 
