@@ -115,7 +115,8 @@ def test_full_size_config_thirty_rounds_free_running():
        max(bar, 4 x the deviation of the oracle's own fp32 mirror from fp64): the mirror is the same
        numpy code run in fp32 on the same inputs, its deviation taken as the running maximum over the
        same (certain) parameters.  While the mirror is still far below the bar this IS the bar
-       1e-4 (1 + |x|); the test requires that to hold for the first six rounds at least."""
+       1e-4 (1 + |x|); and whatever the mirror does (its own rounding depends on the host's BLAS),
+       the device is held to the plain bar outright for the first eight rounds."""
     cfg = synth_inputs.CONFIGS["C4_mlp"]
     W, shape, batch, k = cfg["W"], cfg["mlp"], cfg["batch"], cfg["k"][0]
     hyper = dict(lr=cfg["lr"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"], seed=cfg["seed"])
@@ -145,8 +146,9 @@ def test_full_size_config_thirty_rounds_free_running():
               flush=True)
         assert ex <= bound_x and ev <= bound_v, (r, ex, ev, mx, mv)
         assert loose <= max(5e-3, 4 * ml), (r, loose, ml)
-    print("C4: the plain bar was in force for the first %d rounds" % strict, flush=True)
-    assert strict >= 6
+        if r < 8:
+            assert ex <= TOL and ev <= 10 * TOL, (r, ex, ev)
+    print("C4: by the mirror's evidence the plain bar was in force for the first %d rounds" % strict, flush=True)
     assert (~sure).mean() <= 0.15                   # the accumulated exclusion stays a small part of the model
     assert g.ctx.get_step() == o.step == cfg["rounds"] * k
     g.close()
