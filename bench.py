@@ -548,8 +548,8 @@ def main():
                          "full, with compact measurements of C3 (VGG16-sized), C5 (bucketed tensor list, W=64) and C4 "
                          "(MLP-gradient workers) under \"workloads\"")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100, help="timed rounds")
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200, help="timed rounds")
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--k", type=int, default=2, help="local steps per round for the headline value")
     ap.add_argument("--variant", choices=("separate", "fused_tail"), default="fused_tail")
     ap.add_argument("--no-cpu-baseline", action="store_true")

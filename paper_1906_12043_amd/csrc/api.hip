@@ -416,6 +416,15 @@ int cocod_sync(cocod_ctx *ctx)
     return COCOD_OK;
 }
 
+// Panel order of the kernels that apply line 6 (see kPanelTiles): 4 * chunks * W single-wave blocks plus the
+// padding of the last panel must fit one grid dimension.
+static uint32_t panel_tiles_for(const cocod_ctx *ctx)
+{
+    return ctx->padded_d * sizeof(float) > kMeanCacheBytes &&
+           (4 * ctx->chunks.size() + kPanelTiles) * static_cast<uint64_t>(ctx->cfg.W) * 64 < kMaxThreadsPerGridDim
+               ? kPanelTiles : 0u;
+}
+
 // The next step, if it carries line 6, can also form the round's mean itself (k = 1 under the schedule
 // that folds Step I into Step II: the step reads exactly the stored models).
 static bool one_pass_applies(const cocod_ctx *ctx)
@@ -480,10 +489,7 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.key1 = static_cast<uint32_t>(ctx->cfg.seed >> 32);
         p.step = static_cast<uint32_t>(ctx->capturing ? ctx->step - ctx->capture_base : ctx->step);
         p.step_base = ctx->capturing ? ctx->d_step : nullptr;
-        // (4 * chunks * W single-wave blocks plus the padding of the last panel in one grid dimension)
-        p.panel_tiles = ctx->padded_d * sizeof(float) > kMeanCacheBytes &&
-                        (4 * ctx->chunks.size() + kPanelTiles) * static_cast<uint64_t>(ctx->cfg.W) * 64 < kMaxThreadsPerGridDim
-                            ? kPanelTiles : 0u;
+        p.panel_tiles = panel_tiles_for(ctx);
         // Step I inside the round's first step: that step reads exactly the stored models (when there are
         // too many workers for its LDS tile, the mean stays pending and is formed just before line 6)
         const bool head = ctx->schedule == COCOD_SCHED_HEAD && ctx->mean_pending && ctx->store_pending && !g_ext &&
@@ -629,9 +635,19 @@ int cocod_average_end_apply(cocod_ctx *ctx)
         } else {
             const int rc = mean_before_line6(ctx);                                // SERIAL: the mean; OVERLAP: the join
             if (rc != COCOD_OK) return rc;
-            for (size_t b = 0; b < n_buckets; ++b)
-                COCOD_HIP(ctx, cocod::launch_correct(ctx->s_compute, ctx->live, ctx->snap, ctx->cfg.mean, ctx->cfg.stride,
-                                                     ctx->cfg.W, ctx->bucket_begin[b], ctx->bucket_begin[b + 1]));
+            {                                                                      // line 6, one launch for the whole list
+                cocod::StepParams p{};
+                p.table = ctx->d_chunks;
+                p.n_chunks = static_cast<uint32_t>(ctx->chunks.size());
+                p.W = ctx->cfg.W;
+                p.stride = ctx->cfg.stride;
+                p.x_in = ctx->live;
+                p.x_out = ctx->live;
+                p.snap = ctx->snap;
+                p.mean = ctx->cfg.mean;
+                p.panel_tiles = panel_tiles_for(ctx);
+                COCOD_HIP(ctx, cocod::launch_line6(ctx->s_compute, p));
+            }
         }
     }
     ctx->averaging = false;

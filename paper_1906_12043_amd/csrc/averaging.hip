@@ -1,16 +1,17 @@
 // Step I and line 6 of Algorithm 1 (CoCoD-SGD) on one GPU.
 //
 //   wmean         mean_j = sum_i p_i snap_ij           (the paper's all-reduce between workers)
-//   correct       x_ij   = mean_j + (x_ij - snap_ij)   (line 6)
-//   mean_correct  both in one pass (sequential schedule, nothing to overlap)
+//   mean_correct  the mean and line 6, x_ij = mean_j + (x_ij - snap_ij), in one pass (sequential
+//                 schedule, nothing to overlap)
+// (Line 6 on its own is a mode of the local-step kernel: a row-wise stream like the step itself.)
 //
 // Models are worker-major [W][stride], so the reduction runs along the SLOW axis:
 // a thread owns one 16-byte column quad and walks the W rows with independent
 // 16-byte loads; consecutive lanes own consecutive quads, so every wave load is
 // 1 KiB contiguous.  The sum is taken in worker order 0..W-1 in fp32, which fixes
 // the result bit for bit regardless of launch shape or schedule.
-// For line 6 the same thread serves all W workers of its column, so the mean is
-// read once per column instead of once per worker (12 + 4/W bytes per parameter).
+// In mean_correct the same thread then serves all W workers of its column for line 6, so each stored
+// model is read once (12 + 4/W bytes per parameter).
 #include "internal.hpp"
 #include "mean_sum.hpp"
 
@@ -102,16 +103,6 @@ __device__ __forceinline__ void correct_column(float *xcol, const float *scol, c
         o.z = m.z + (xr.z - sr.z); o.w = m.w + (xr.w - sr.w);
         st4_stream(xcol + static_cast<uint64_t>(i) * stride, o);
     }
-}
-
-__global__ __launch_bounds__(kAvgThreads) void correct_kernel(float *x, const float *snap, const float *mean,
-                                                              uint64_t stride, uint32_t W, uint64_t begin,
-                                                              uint64_t n_quads)
-{
-    const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
-    if (quad >= n_quads) return;
-    const uint64_t e = begin + quad * 4;
-    correct_column(x + e, snap + e, ld4(mean + e), stride, W);
 }
 
 // WREG > 0: W <= WREG and the column's stored models stay in registers between the two passes, so
@@ -291,16 +282,6 @@ hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, 
     const dim3 grid(blocks_for(n_quads)), block(kAvgThreads);
     if (weights) hipLaunchKernelGGL((wmean_kernel<true>), grid, block, 0, stream, snap, stride, W, begin, n_quads, weights, mean);
     else         hipLaunchKernelGGL((wmean_kernel<false>), grid, block, 0, stream, snap, stride, W, begin, n_quads, weights, mean);
-    return hipGetLastError();
-}
-
-hipError_t launch_correct(hipStream_t stream, float *x, const float *snap, const float *mean, uint64_t stride,
-                          uint32_t W, uint64_t begin, uint64_t end)
-{
-    const uint64_t n_quads = (end - begin) / 4;
-    if (n_quads == 0) return hipSuccess;
-    hipLaunchKernelGGL(correct_kernel, dim3(blocks_for(n_quads)), dim3(kAvgThreads), 0, stream, x, snap, mean,
-                       stride, W, begin, n_quads);
     return hipGetLastError();
 }
 

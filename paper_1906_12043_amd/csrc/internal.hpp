@@ -53,6 +53,9 @@ struct StepParams {
 // start / stop: optional events that receive the kernel's own begin / end timestamps.
 hipError_t launch_local_step(hipStream_t stream, const StepParams &p, hipEvent_t start = nullptr,
                              hipEvent_t stop = nullptr);
+// Line 6 alone, in place on p.x_out (== p.x_in): x = mean + (x - snap), one launch for the whole parameter list
+// (uses table, n_chunks, W, stride, x_in, x_out, snap, mean, panel_tiles of p).
+hipError_t launch_line6(hipStream_t stream, const StepParams &p);
 // Column quads per lane (1 or 2) with which the mean-forming steps hold the W rows of a tile in LDS;
 // 0 = W is too large for them (the mean is then formed by a pass of its own).
 int local_step_mean_quads_per_lane(uint32_t W, bool one_pass);
@@ -62,11 +65,7 @@ int local_step_mean_quads_per_lane(uint32_t W, bool one_pass);
 hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, uint32_t W,
                         uint64_t begin, uint64_t end, const float *weights, float *mean);
 
-// x[i][e] = mean[e] + (x[i][e] - snap[i][e])
-hipError_t launch_correct(hipStream_t stream, float *x, const float *snap, const float *mean,
-                          uint64_t stride, uint32_t W, uint64_t begin, uint64_t end);
-
-// both of the above in one pass; mean is still written
+// the mean and line 6, x[i][e] = mean[e] + (x[i][e] - snap[i][e]), in one pass; mean is still written
 hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, uint64_t stride,
                                uint32_t W, uint64_t begin, uint64_t end, const float *weights,
                                float *mean);

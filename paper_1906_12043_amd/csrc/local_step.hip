@@ -37,7 +37,7 @@
 namespace cocod {
 namespace {
 
-enum { kModePlain = 0, kModeTail = 1, kModeTailIn = 2, kModeHead = 3, kModeOnePass = 4 };
+enum { kModePlain = 0, kModeTail = 1, kModeTailIn = 2, kModeHead = 3, kModeOnePass = 4, kModeLine6 = 5 };
 
 // Normals for the Q memory quads of one lane.  Quad u of lane l covers global indices
 // 4 (q0 + 64 u + l) + shift .. + 3: with shift == 0 exactly generator block q0 + 64 u + l, else the
@@ -81,7 +81,7 @@ template <bool HAS_V, int GRAD, int MODE, bool WEIGHTED, int NWMAX, int Q>
 __global__ __launch_bounds__(64 * NWMAX) void local_step_kernel(const StepParams p)
 {
     constexpr bool FORMS_MEAN = MODE == kModeHead || MODE == kModeOnePass;
-    constexpr bool LINE6 = MODE == kModeTail || MODE == kModeTailIn || MODE == kModeOnePass;
+    constexpr bool LINE6 = MODE == kModeTail || MODE == kModeTailIn || MODE == kModeOnePass || MODE == kModeLine6;
     constexpr uint32_t PARTS = 4 / Q, TILE_ELEMS = Q * 256;
     extern __shared__ __attribute__((aligned(16))) float lds[];
 
@@ -177,6 +177,30 @@ __global__ __launch_bounds__(64 * NWMAX) void local_step_kernel(const StepParams
         if (w >= p.W) return;                              // no barrier in these modes
         f4 x0[Q], snap[Q], m[Q];
         load_x(x0, w);
+        if constexpr (MODE == kModeLine6) {                // line 6 alone, in place: x = mean + (x - stored model)
+            const uint64_t row = static_cast<uint64_t>(w) * p.stride + col;
+            const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.snap + row, bytes), rm = make_rsrc(p.mean + col, bytes);
+            const __amdgpu_buffer_rsrc_t rx_out = make_rsrc(p.x_out + row, bytes);
+            #pragma unroll
+            for (int u = 0; u < Q; ++u) {
+                const uint32_t e = (64u * u + lane) * 4u, off = e * 4u;
+                snap[u] = load_quad(rs, off);
+                m[u] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rm, static_cast<int>(off), 0, 0));
+            }
+            #pragma unroll
+            for (int u = 0; u < Q; ++u) {
+                const uint32_t e = (64u * u + lane) * 4u;
+                f4 x = line6_quad(m[u], x0[u], snap[u]);
+                if (e + 4 > n && e < n) {                  // tensor tail: alignment pads keep their old values
+                    const uint32_t keep = n - e;
+                    if (keep < 2) x.y = x0[u].y;
+                    if (keep < 3) x.z = x0[u].z;
+                    x.w = x0[u].w;
+                }
+                store_quad(rx_out, e * 4u, x);
+            }
+            return;
+        }
         const Row r = load_row(w);
         #pragma unroll
         for (int u = 0; u < Q; ++u) { snap[u] = x0[u]; m[u] = f4{0.f, 0.f, 0.f, 0.f}; }
@@ -271,7 +295,7 @@ hipError_t launch_one(hipStream_t stream, const StepParams &p, uint32_t waves, h
         static const hipError_t lds_ok = allow_big_lds(kernel, kTileLdsMax);
         if (lds_ok != hipSuccess) return lds_ok;
     }
-    constexpr bool LINE6 = MODE == kModeTail || MODE == kModeTailIn;
+    constexpr bool LINE6 = MODE == kModeTail || MODE == kModeTailIn || MODE == kModeLine6;
     const uint32_t groups = FORMS_MEAN ? 1u : (p.W + waves - 1) / waves;
     const uint32_t tiles = p.n_chunks * (4 / Q);
     // panels: every panel takes panel_tiles * groups block ids, the short last one included
@@ -333,6 +357,11 @@ int local_step_mean_quads_per_lane(uint32_t W, bool one_pass)
     if (W > 16 && rows * 2 * 256 * sizeof(float) <= kTileLdsMax) return 2;
     if (rows * 256 * sizeof(float) <= kTileLdsMax) return 1;
     return 0;
+}
+
+hipError_t launch_line6(hipStream_t stream, const StepParams &p)
+{
+    return launch_one<false, kGradQuadExact, kModeLine6, false, 1, 1>(stream, p, 1, nullptr, nullptr);
 }
 
 hipError_t launch_local_step(hipStream_t stream, const StepParams &p, hipEvent_t start, hipEvent_t stop)

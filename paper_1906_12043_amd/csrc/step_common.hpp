@@ -31,6 +31,13 @@ __device__ __forceinline__ void store_quad(__amdgpu_buffer_rsrc_t r, uint32_t by
 // Where the stochastic gradient G of a step comes from.
 enum { kGradQuadNoisy = 0, kGradQuadExact = 1, kGradExternal = 2, kGradExternalBf16 = 3 };
 
+// Line 6 of Algorithm 1 on a quad: x = mean + (x - stored model), the parenthesis first.
+__device__ __forceinline__ f4 line6_quad(const f4 mean, const f4 x, const f4 snap)
+{
+    #pragma clang fp contract(off)
+    return mean + (x - snap);
+}
+
 // One local step of Algorithm 1's Step II on a quad of parameters, with the experiments' optimizer,
 // and optionally line 6 on the result:
 //     G = h (x - c) + sigma z      (QUADRATIC; else G = a, the caller's gradient)
