@@ -84,8 +84,8 @@ enum {
  * has padded_d = d rounded up to 4.  A parameter list of n_tensors tensors is
  * packed in list order, each tensor starting on a 4 KiB boundary (offset multiple
  * of 1024 elements) and the end of the list rounded up to 4; see
- * cocod_plan_layout.  The elements in the gaps are pads: the local step never
- * touches them, the averaging kernels carry them along, and they never
+ * cocod_plan_layout.  The elements in the gaps are pads: the local step and line 6
+ * never touch them, the mean kernels may carry them along, and they never
  * influence real elements (their contents are unspecified).  For full memory
  * bandwidth choose stride as a multiple of 1024 elements, so that every
  * worker's row starts on a 4 KiB boundary as well (any multiple of 4 is legal).
@@ -279,8 +279,8 @@ int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks,
  * context); n = 0 switches it off.  cocod_step_timing_read waits for compute_stream, returns the
  * summed kernel durations and the number of launches measured since the last read, and rearms.
  * Index 0 of both arrays: plain local steps; index 1: steps that carry line 6
- * (cocod_local_steps_end_apply's last step); index 2: first steps of a round that also form the
- * mean (COCOD_SCHED_HEAD).
+ * (cocod_local_steps_end_apply's last step, the one-pass k = 1 step included); index 2: first steps
+ * of a round that also form the mean (COCOD_SCHED_HEAD).
  */
 int cocod_step_timing(cocod_ctx *ctx, int max_launches);
 int cocod_step_timing_read(cocod_ctx *ctx, double total_ms[3], uint32_t launches[3]);
