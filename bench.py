@@ -475,7 +475,7 @@ def bench_mlp(k, variant, steps, warmup, full):
         "line6_step_ms": tail_s * 1e3 if tail_s else None,
         "local_step_TFLOPs_all": all_flops / step_s / 1e12,
         "local_step_hbm_GBps": step_hbm_bytes / step_s / 1e9,
-        "roofline": {"bound": "mfma", "kernel": "one local step (5 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
+        "roofline": {"bound": "mfma", "kernel": "one local step (4 launches; mlp_gemm_kernel<fwd>, <bwd> carry the flops)",
                      "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": step_s * 1e3,
                      "launches_timed": steps * k, "algorithmic_flops_per_launch": gemm_flops},

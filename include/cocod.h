@@ -337,6 +337,9 @@ int cocod_fill_quadratic(cocod_ctx *ctx);
  *   dA [W][batch][mlp_hidden] gradient at the hidden pre-activation,
  *   dZ [W][batch][*dz_pitch] gradient at the logits (first mlp_out entries of each row),
  *   y [W][batch] labels.
+ * X and y are those of the most recent local step: the context keeps two mini-batch buffers (a step
+ * draws the next step's batch into the other one while its output layer runs), so the two pointers
+ * change from step to step - ask again after each.
  */
 int cocod_mlp_workspace(const cocod_ctx *ctx, float **X, float **H, float **dA, float **dZ, int32_t **y,
                         uint32_t *dz_pitch);

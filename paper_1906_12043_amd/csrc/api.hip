@@ -28,6 +28,13 @@ struct cocod_ctx {
     double *static_scratch = nullptr;   // this GPU's copy of the library's static scratch array (not owned)
     float *mlp_ws = nullptr;            // MLP kind: work space (owned); mlp holds the pointers carved from it
     cocod::MlpParams mlp{};
+    // MLP kind: two mini-batch buffers.  A local step draws the NEXT step's batch into the other one while
+    // its output layer runs, so that only the first step after anything else draws its own up front.
+    float *mlp_X[2] = {nullptr, nullptr};
+    int32_t *mlp_y[2] = {nullptr, nullptr};
+    uint32_t batch_buf = 0;             // buffer the next eager step takes its batch from
+    uint32_t batch_last = 0;            // buffer the most recent step took its batch from
+    uint64_t batch_ready_step = ~0ull;  // mlp_X[batch_buf] holds the batch of this step index (~0: of none)
     hipEvent_t ev_snap = nullptr;       // compute stream reached the point where the models are stored
     hipEvent_t ev_mean = nullptr;       // mean of the stored models is complete
     hipStream_t s_compute = nullptr, s_avg = nullptr;
@@ -45,7 +52,7 @@ struct cocod_ctx {
     std::vector<char> t_kind;           // per timed launch: 0 plain step, 1 step with line 6
     size_t t_used = 0;
     // replayable rounds: one instantiated graph per (k, variant, schedule, which buffer is live)
-    struct RoundGraph { int k; int fused_tail; int schedule; bool live_is_A; hipGraphExec_t exec; };
+    struct RoundGraph { int k; int fused_tail; int schedule; bool live_is_A; uint32_t batch_buf; bool batch_ready; hipGraphExec_t exec; };
     std::vector<RoundGraph> graphs;     // owned
     uint32_t *d_step = nullptr;         // device copy of t that captured kernels read (owned)
     uint64_t d_step_value = ~0ull;      // what *d_step holds once the work queued on the compute stream has run
@@ -370,14 +377,18 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         if (e == hipSuccess && cfg->grad == COCOD_GRAD_MLP) {      // one work-space block, carved below
             const size_t wb = static_cast<size_t>(cfg->W) * cfg->mlp_batch;
             const size_t n_x = wb * cfg->mlp_in, n_h = wb * cfg->mlp_hidden, n_z = wb * cocod::mlp_dz_pitch();
-            e = hipMalloc(reinterpret_cast<void **>(&ctx->mlp_ws), (n_x + 2 * n_h + n_z + wb) * sizeof(float));
+            e = hipMalloc(reinterpret_cast<void **>(&ctx->mlp_ws), (2 * n_x + 2 * n_h + n_z + 2 * wb) * sizeof(float));
             if (e == hipSuccess) {
                 float *at = ctx->mlp_ws;
-                ctx->mlp.X = at;  at += n_x;
+                ctx->mlp_X[0] = at; at += n_x;
+                ctx->mlp_X[1] = at; at += n_x;
                 ctx->mlp.H = at;  at += n_h;
                 ctx->mlp.dA = at; at += n_h;
                 ctx->mlp.dZ = at; at += n_z;
-                ctx->mlp.y = reinterpret_cast<int32_t *>(at);
+                ctx->mlp_y[0] = reinterpret_cast<int32_t *>(at); at += wb;
+                ctx->mlp_y[1] = reinterpret_cast<int32_t *>(at);
+                ctx->mlp.X = ctx->mlp_X[0];
+                ctx->mlp.y = ctx->mlp_y[0];
             }
         }
         if (e == hipSuccess) e = scratch_for_current_device(&ctx->static_scratch);
@@ -442,6 +453,15 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
     float *dst = ctx->store_pending ? ctx->spare : ctx->live;
     if (!ctx->dry && ctx->cfg.grad == COCOD_GRAD_MLP && !g_ext) {
         cocod::MlpParams p = ctx->mlp;             // work-space pointers
+        // Mini-batch buffers: steps alternate between the two, and the context remembers for which step
+        // index the next one is already filled (a captured round is keyed by both facts as they stand at
+        // its first step, and leaves them as the same eager calls would).
+        const uint32_t buf = ctx->batch_buf;
+        p.X = ctx->mlp_X[buf];
+        p.y = ctx->mlp_y[buf];
+        p.X_next = ctx->mlp_X[buf ^ 1u];
+        p.y_next = ctx->mlp_y[buf ^ 1u];
+        p.have_batch = ctx->batch_ready_step == ctx->step;
         p.W = ctx->cfg.W;
         p.n_in = ctx->cfg.mlp_in; p.n_hid = ctx->cfg.mlp_hidden; p.n_out = ctx->cfg.mlp_out; p.batch = ctx->cfg.mlp_batch;
         p.stride = ctx->cfg.stride;
@@ -460,6 +480,9 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         const bool timed = ctx->timing && ctx->t_used < ctx->t_start.size();
         if (timed) COCOD_HIP(ctx, hipEventRecord(ctx->t_start[ctx->t_used], ctx->s_compute));
         COCOD_HIP(ctx, cocod::launch_mlp_step(ctx->s_compute, p));
+        ctx->batch_last = buf;
+        ctx->batch_buf = buf ^ 1u;
+        ctx->batch_ready_step = ctx->step + 1;
         if (timed) {
             COCOD_HIP(ctx, hipEventRecord(ctx->t_stop[ctx->t_used], ctx->s_compute));
             ctx->t_kind[ctx->t_used] = with_line6 ? 1 : 0;
@@ -689,6 +712,8 @@ static int capture_round(cocod_ctx *ctx, int k, int fused_tail, hipGraphExec_t *
     float *const live = ctx->live, *const spare = ctx->spare;
     const uint64_t step = ctx->step;
     const bool timing = ctx->timing;
+    const uint32_t batch_buf = ctx->batch_buf, batch_last = ctx->batch_last;
+    const uint64_t batch_ready_step = ctx->batch_ready_step;
     ctx->timing = false;
     ctx->capturing = true;
     ctx->capture_base = step;
@@ -715,6 +740,7 @@ static int capture_round(cocod_ctx *ctx, int k, int fused_tail, hipGraphExec_t *
     ctx->live = live; ctx->spare = spare; ctx->snap = nullptr;
     ctx->averaging = false; ctx->store_pending = false; ctx->mean_pending = false;
     ctx->step = step;
+    ctx->batch_buf = batch_buf; ctx->batch_last = batch_last; ctx->batch_ready_step = batch_ready_step;
     ctx->timing = timing;
     ctx->capturing = false;
     if (rc == COCOD_OK) {
@@ -744,13 +770,17 @@ int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail)
     }
     if (!ctx->d_step) COCOD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->d_step), sizeof(uint32_t)));
     const bool live_is_A = ctx->live == ctx->cfg.xA;
+    const bool mlp = ctx->cfg.grad == COCOD_GRAD_MLP && k > 0;
+    const uint32_t batch_buf = mlp ? ctx->batch_buf : 0u;                    // which mini-batch buffer the first step reads,
+    const bool batch_ready = mlp && ctx->batch_ready_step == ctx->step;      // and whether its batch is already there
     hipGraphExec_t exec = nullptr;
     for (const auto &g : ctx->graphs)
-        if (g.k == k && g.fused_tail == fused_tail && g.schedule == ctx->schedule && g.live_is_A == live_is_A) exec = g.exec;
+        if (g.k == k && g.fused_tail == fused_tail && g.schedule == ctx->schedule && g.live_is_A == live_is_A &&
+            g.batch_buf == batch_buf && g.batch_ready == batch_ready) exec = g.exec;
     if (!exec) {
         rc = capture_round(ctx, k, fused_tail, &exec);
         if (rc != COCOD_OK) return rc;
-        ctx->graphs.push_back({k, fused_tail, ctx->schedule, live_is_A, exec});
+        ctx->graphs.push_back({k, fused_tail, ctx->schedule, live_is_A, batch_buf, batch_ready, exec});
     }
     if (ctx->d_step_value != ctx->step) {            // eager calls since the last replay moved t
         COCOD_HIP(ctx, cocod::launch_set_word(ctx->s_compute, ctx->d_step, static_cast<uint32_t>(ctx->step)));
@@ -761,6 +791,11 @@ int cocod_graph_round(cocod_ctx *ctx, int k, int fused_tail)
         float *t = ctx->live; ctx->live = ctx->spare; ctx->spare = t;
         ctx->step += static_cast<uint64_t>(k);
         ctx->d_step_value = ctx->step;
+        if (mlp) {                                   // k steps alternated the batch buffers; the last drew the next batch
+            ctx->batch_last = (batch_buf + static_cast<uint32_t>(k - 1)) & 1u;
+            ctx->batch_buf = ctx->batch_last ^ 1u;
+            ctx->batch_ready_step = ctx->step;
+        }
     }
     return COCOD_OK;
 }
@@ -920,11 +955,11 @@ int cocod_mlp_workspace(const cocod_ctx *ctx, float **X, float **H, float **dA, 
 {
     if (!ctx) return fail(nullptr, COCOD_ERR_INVALID, "ctx is NULL");
     if (ctx->cfg.grad != COCOD_GRAD_MLP) return fail(nullptr, COCOD_ERR_INVALID, "not an MLP-gradient context");
-    if (X) *X = ctx->mlp.X;
+    if (X) *X = ctx->mlp_X[ctx->batch_last];
     if (H) *H = ctx->mlp.H;
     if (dA) *dA = ctx->mlp.dA;
     if (dZ) *dZ = ctx->mlp.dZ;
-    if (y) *y = ctx->mlp.y;
+    if (y) *y = ctx->mlp_y[ctx->batch_last];
     if (dz_pitch) *dz_pitch = static_cast<uint32_t>(cocod::mlp_dz_pitch());
     return COCOD_OK;
 }

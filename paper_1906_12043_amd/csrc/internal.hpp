@@ -97,7 +97,10 @@ struct MlpParams {
     const float *snap;        // non-null: last step of a round; line 6 is applied to every updated parameter
     const float *mean;        //           before it is stored: x = mean + (x_new - snap)   (mean is [stride])
     // work space owned by the context
-    float *X;                 // [W][batch][n_in]
+    float *X;                 // [W][batch][n_in]   this step's mini-batch
+    float *X_next;            // same shape, the other batch buffer: the step also draws the NEXT step's
+    int32_t *y_next;          //   mini-batch and labels into these (null: it does not)
+    bool have_batch;          // X and y already hold this step's mini-batch (drawn by the previous step)
     float *H;                 // [W][batch][n_hid]  relu output
     float *dA;                // [W][batch][n_hid]  gradient at the hidden pre-activation
     float *dZ;                // [W][batch][mlp_dz_pitch()]  gradient at the logits

@@ -2,12 +2,15 @@
 // perceptron  A = X W1 + b1, H = relu(A), Z = H W2 + b2, loss = mean softmax cross-entropy,
 // on a fresh seeded mini-batch per (worker, step); all W workers advance in the same launches.
 //
-// One local step = five launches on the compute stream:
-//   gen_batch      X and labels from the counter-based generator                 (vector ALU)
+// One local step = four launches on the compute stream (five for a step whose mini-batch no earlier
+// step has drawn: gen_batch in front):
 //   gemm<FWD>      H = relu(X W1 + b1)                         [B x in] x [in x hid]   fp32 MFMA
 //   head           Z = H W2 + b2, softmax, dZ = (P - onehot)/B, dA = (dZ W2^T) * [H > 0]
 //                  (one wave per sample, wave reductions, W2 in LDS)
-//   head_update    dW2 = H^T dZ, db2, db1 = colsum(dA); momentum-SGD update of W2, b2, b1
+//   head_update    dW2 = H^T dZ, db2, db1 = colsum(dA); momentum-SGD update of W2, b2, b1;
+//                  further blocks of the same launch draw the NEXT step's X and labels from the
+//                  counter-based generator into the other of two batch buffers (vector ALU work
+//                  beside a kernel that is a short chain of dependent loads)
 //   gemm<BWD>      dW1 = X^T dA with the momentum-SGD update of W1 fused into the epilogue
 //                  (the 12.6 MB gradient of W1 never goes to memory)   [in x B] x [B x hid]  fp32 MFMA
 // The two big contractions (98 % of the flops) run on the matrix cores; the output layer has
@@ -67,24 +70,36 @@ __device__ __forceinline__ void sgd_update(const MlpParams &p, uint64_t at, floa
 // ---- mini-batch ---------------------------------------------------------------------------------
 // X[b][f] = normal(stream X, worker, step, flat index b*n_in + f);
 // y[b] = (word * n_out) >> 32 from stream Y at index b.
-__global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
+// One 256-thread block's share of a worker's mini-batch for local step `step`: 256 quads of X, and in
+// block 0 the labels.
+__device__ __forceinline__ void gen_batch_block(const MlpParams &p, uint32_t block, uint32_t worker, uint32_t step,
+                                                float *X_all, int32_t *y_all)
 {
-    const uint32_t worker = blockIdx.y;
-    const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;
     const uint64_t n_quads = static_cast<uint64_t>(p.batch) * p.n_in / 4;
-    const uint64_t q = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const uint64_t q = static_cast<uint64_t>(block) * 256 + threadIdx.x;
     if (q < n_quads) {
         const Normals4 z = box_muller_fast(philox4x32_10(static_cast<uint32_t>(q), step, worker, kTagMlpX, p.key0, p.key1));
-        float *X = p.X + static_cast<uint64_t>(worker) * p.batch * p.n_in;
+        float *X = X_all + static_cast<uint64_t>(worker) * p.batch * p.n_in;
         *reinterpret_cast<f4 *>(X + q * 4) = f4{z.z[0], z.z[1], z.z[2], z.z[3]};
     }
-    if (blockIdx.x == 0 && threadIdx.x < p.batch / 4) {
+    if (block == 0 && threadIdx.x < p.batch / 4) {
         const Words4 r = philox4x32_10(threadIdx.x, step, worker, kTagMlpY, p.key0, p.key1);
         #pragma unroll
         for (int i = 0; i < 4; ++i)
-            p.y[static_cast<uint64_t>(worker) * p.batch + threadIdx.x * 4 + i] =
+            y_all[static_cast<uint64_t>(worker) * p.batch + threadIdx.x * 4 + i] =
                 static_cast<int32_t>((static_cast<uint64_t>(r.w[i]) * p.n_out) >> 32);
     }
+}
+
+__host__ __device__ inline uint32_t gen_batch_blocks(const MlpParams &p)
+{
+    return static_cast<uint32_t>((static_cast<uint64_t>(p.batch) * p.n_in / 4 + 255) / 256);
+}
+
+__global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
+{
+    const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;
+    gen_batch_block(p, blockIdx.x, blockIdx.y, step, p.X, p.y);
 }
 
 // ---- the two big contractions ---------------------------------------------------------------------
@@ -478,6 +493,15 @@ __global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
 {
     __shared__ float part[4][64][NOUT + 1];
     const uint32_t worker = blockIdx.y;
+    // The blocks behind the (n_hid + 63) / 64 that own hidden units draw the NEXT local step's mini-batch
+    // into the other batch buffer: this kernel is a short chain of dependent loads on one block per
+    // compute unit, and the generator is pure vector arithmetic that fills the rest of the chip meanwhile.
+    const uint32_t own_blocks = (p.n_hid + 63) / 64;
+    if (blockIdx.x >= own_blocks) {
+        const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;
+        gen_batch_block(p, blockIdx.x - own_blocks, worker, step + 1, p.X_next, p.y_next);
+        return;
+    }
     const uint32_t u = threadIdx.x % 64, slice = threadIdx.x / 64;
     const uint32_t n = blockIdx.x * 64 + u;
     const Offsets o = offsets_of(p);
@@ -564,7 +588,8 @@ hipError_t launch_heads_for(hipStream_t stream, const MlpParams &p)
     if (lds_ok != hipSuccess) return lds_ok;
     hipLaunchKernelGGL(head_kernel<NOUT>, dim3((p.batch + kHeadSamples - 1) / kHeadSamples, p.W), dim3(256),
                        static_cast<size_t>(p.n_hid) * head_w2_pitch(NOUT) * sizeof(float), stream, p);
-    hipLaunchKernelGGL(head_update_kernel<NOUT>, dim3((p.n_hid + 63) / 64, p.W), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(head_update_kernel<NOUT>, dim3((p.n_hid + 63) / 64 + (p.X_next ? gen_batch_blocks(p) : 0u), p.W),
+                       dim3(256), 0, stream, p);
     return hipSuccess;
 }
 
@@ -590,9 +615,8 @@ size_t mlp_dz_pitch() { return kMaxOut; }
 
 hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
 {
-    const uint64_t n_quads = static_cast<uint64_t>(p.batch) * p.n_in / 4;
     const bool wide = p.n_hid % 128 == 0;      // 64 x 128 block tiles (fastest measured), else 64 x 64
-    hipLaunchKernelGGL(gen_batch_kernel, dim3(static_cast<uint32_t>((n_quads + 255) / 256), p.W), dim3(256), 0, stream, p);
+    if (!p.have_batch) hipLaunchKernelGGL(gen_batch_kernel, dim3(gen_batch_blocks(p), p.W), dim3(256), 0, stream, p);
     if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
     const hipError_t head_rc = launch_heads(stream, p, std::make_integer_sequence<int, kMaxOut>{});
     if (head_rc != hipSuccess) return head_rc;

@@ -106,13 +106,22 @@ def test_contexts_release_what_they_own():
     assert free0 - free1 < (8 << 20), (free0, free1)
 
 
-def test_graph_rounds_of_mlp_workers_match_eager_rounds_and_oracle():
-    W, shape, batch, k, rounds = 3, (128, 64, 10), 128, 2, 5
+@pytest.mark.parametrize("k", [2, 3])
+def test_graph_rounds_of_mlp_workers_match_eager_rounds_and_oracle(k):
+    """Graph-replayed and eager rounds mixed in one context against eager rounds only.  A local step draws the
+    next step's mini-batch into the other of two buffers, and a captured round is keyed by which buffer its
+    first step reads and whether that batch is already there: odd k alternates the first, the eager round
+    and the jump of the step counter in between change the second."""
+    W, shape, batch, rounds = 3, (128, 64, 10), 128, 7
     theta0 = synth_inputs.mlp_he_init(11, *shape)
     hyper = dict(lr=0.05, momentum=0.9, weight_decay=1e-3, seed=0x5EED0004)
     e, g = GpuMlp(W, shape, batch, theta0, **hyper), GpuMlp(W, shape, batch, theta0, **hyper)
     o = mlp_oracle.MlpOracle(theta0, W, *shape, batch, **hyper)
     for r in range(rounds):
+        if r == 4:                                   # the batch drawn ahead is now for a step that never comes
+            for side in (e.ctx, g.ctx):
+                side.set_step(side.get_step() + 5)
+            o.step += 5
         e.ctx.round(k)
         if r == 2:
             g.ctx.round(k)
@@ -121,5 +130,9 @@ def test_graph_rounds_of_mlp_workers_match_eager_rounds_and_oracle():
         o.round(k)
         assert np.array_equal(e.x(), g.x()) and np.array_equal(e.vel(), g.vel()), r
         assert e.ctx.get_step() == g.ctx.get_step() == o.step
+        ws = g.workspace()                           # the batch the round's last step used is that step's own
+        for i in range(W):
+            X, y = mlp_oracle.minibatch(hyper["seed"], i, o.step - 1, batch, shape[0], shape[2])
+            assert np.array_equal(ws["y"][i], y) and np.max(np.abs(ws["X"][i] - X)) < 2e-6, (r, i)
     assert rel_err(g.x(), o.x) <= 1e-4 and rel_err(g.vel(), o.v) <= 1e-4
     e.close(); g.close()

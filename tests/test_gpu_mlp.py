@@ -49,6 +49,32 @@ def test_pieces_of_one_step(W, shape, batch):
     g.close()
 
 
+def test_every_step_trains_on_its_own_minibatch():
+    """A local step draws the NEXT step's mini-batch beside its output layer, into the other of two buffers.
+    Whatever precedes a step - another step, a jump of the step counter, a round boundary - the batch it
+    used (read back from the work space) is the one keyed by its own step index."""
+    W, shape, batch = 2, (128, 64, 10), 128
+    g = GpuMlp(W, shape, batch, synth_inputs.mlp_he_init(3, *shape), **HYPER)
+
+    def check(step):
+        ws = g.workspace()
+        for i in range(W):
+            X, y = mlp.minibatch(HYPER["seed"], i, step, batch, shape[0], shape[2])
+            assert np.array_equal(ws["y"][i], y), (step, i)
+            assert np.max(np.abs(ws["X"][i] - X)) < 2e-6, (step, i)
+
+    g.ctx.local_steps(1); check(0)
+    g.ctx.local_steps(3); check(3)
+    g.ctx.set_step(40)                               # the batch drawn ahead (for step 4) must not be used
+    g.ctx.local_steps(2); check(41)
+    g.ctx.round(3); check(44)
+    g.ctx.set_step(45)                               # same value as the counter already has: the batch drawn ahead is right
+    g.ctx.round_fused_tail(1); check(45)
+    g.ctx.set_step(3)
+    g.ctx.local_steps(1); check(3)
+    g.close()
+
+
 @pytest.mark.parametrize("W,shape,batch,k", [(3, (128, 64, 10), 128, 2), (2, (256, 192, 3), 256, 1), (4, (384, 128, 16), 128, 3)])
 def test_small_networks_rounds(W, shape, batch, k):
     theta0 = synth_inputs.mlp_he_init(11, *shape)
