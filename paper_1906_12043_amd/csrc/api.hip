@@ -167,6 +167,9 @@ int plan(uint64_t d, uint32_t n_tensors, const uint64_t *numel, uint64_t bucket_
         at += n;
     }
     padded_d = round_up4(at);
+    if (padded_d > (1ull << 34))            // the chunk table addresses memory in 32-bit quad offsets
+        return fail(nullptr, COCOD_ERR_INVALID, "the padded parameter list holds %llu elements, more than 2^34",
+                    (unsigned long long)padded_d);
     const uint64_t cap = bucket_bytes / sizeof(float);
     bucket_begin.push_back(0);
     uint64_t bucket_start = 0;

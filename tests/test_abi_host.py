@@ -86,7 +86,9 @@ def test_plan_layout_small_cases(sizes, bucket):
 
 
 def test_plan_layout_errors():
-    for d, sizes in [(0, None), (1 << 34, None), (10, [5, 4]), (10, [10, 0])]:
+    # the last case: d itself is in range, but the second tensor starts on a 1024-element boundary and the
+    # padded list then passes 2^34 elements, which 32-bit quad offsets cannot address
+    for d, sizes in [(0, None), (1 << 34, None), (10, [5, 4]), (10, [10, 0]), ((1 << 34) - 4, [1, (1 << 34) - 5])]:
         with pytest.raises(P.CocodError) as e:
             P.plan_layout(d, sizes)
         assert e.value.status == P.ERR_INVALID
