@@ -95,8 +95,8 @@ typedef struct cocod_config {
     uint32_t W;                    /* number of workers N of Algorithm 1, >= 1 */
     uint64_t d;                    /* parameters per worker (sum of tensor sizes), >= 1, < 2^34; and
                                       W * ceil(d / 1024) <= 2^31 - 1 (blocks of one launch; tensors of a
-                                      list each round up on their own); a list's padded extent (every
-                                      tensor starts on a 1024-element boundary) must not exceed 2^34 */
+                                      list each round up on their own); the padded extent (every tensor
+                                      of a list starts on a 1024-element boundary) must not exceed 2^34 - 1024 */
     uint32_t n_tensors;            /* 0 or 1: one flat vector; else length of tensor_numel */
     uint32_t grad;                 /* cocod_grad_kind */
     const uint64_t *tensor_numel;  /* host, [n_tensors], each >= 1, sum == d; copied */

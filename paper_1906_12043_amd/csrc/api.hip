@@ -167,8 +167,10 @@ int plan(uint64_t d, uint32_t n_tensors, const uint64_t *numel, uint64_t bucket_
         at += n;
     }
     padded_d = round_up4(at);
-    if (padded_d > (1ull << 34))            // the chunk table addresses memory in 32-bit quad offsets
-        return fail(nullptr, COCOD_ERR_INVALID, "the padded parameter list holds %llu elements, more than 2^34",
+    // fewer than 2^24 chunks: the chunk table addresses memory in 32-bit quad offsets, and four single-wave
+    // blocks (or one 256-thread block) per chunk must stay below 2^32 threads in one grid dimension
+    if (padded_d > (1ull << 34) - cocod::kChunkElems)
+        return fail(nullptr, COCOD_ERR_INVALID, "the padded parameter list holds %llu elements, more than 2^34 - 1024",
                     (unsigned long long)padded_d);
     const uint64_t cap = bucket_bytes / sizeof(float);
     bucket_begin.push_back(0);
@@ -347,7 +349,7 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
         global += ctx->tensor_numel[t];
     }
     // Launch limits.  A grid dimension holds fewer than 2^32 THREADS.  The (tiles, workers) grid of the local
-    // step has up to four single-wave blocks per chunk in x (chunks < 2^24 is implied by d < 2^34) and W <= 65535
+    // step has up to four single-wave blocks per chunk in x (fewer than 2^24 chunks: checked with the layout) and W <= 65535
     // in y (checked above); the orders that put more into ONE dimension (panels of a line-6 step, 1024-thread
     // blocks of the mean-forming steps) are only used below that limit (see enqueue_step).  The total is capped
     // as well, so that block counts stay inside 32-bit arithmetic everywhere.

@@ -86,9 +86,10 @@ def test_plan_layout_small_cases(sizes, bucket):
 
 
 def test_plan_layout_errors():
-    # the last case: d itself is in range, but the second tensor starts on a 1024-element boundary and the
-    # padded list then passes 2^34 elements, which 32-bit quad offsets cannot address
-    for d, sizes in [(0, None), (1 << 34, None), (10, [5, 4]), (10, [10, 0]), ((1 << 34) - 4, [1, (1 << 34) - 5])]:
+    # the last two: d itself is in range, but the padded list (the second tensor starts on a 1024-element
+    # boundary) passes 2^34 - 1024 elements = 2^24 - 1 chunks, the most one launch and 32-bit quad offsets take
+    for d, sizes in [(0, None), (1 << 34, None), (10, [5, 4]), (10, [10, 0]), ((1 << 34) - 4, None),
+                     ((1 << 34) - 1024, [1, (1 << 34) - 1025])]:
         with pytest.raises(P.CocodError) as e:
             P.plan_layout(d, sizes)
         assert e.value.status == P.ERR_INVALID
@@ -320,7 +321,7 @@ def test_diagnostics_on_dry_contexts():
 def test_launch_size_limits():
     """One block per (chunk of 1024 elements, worker): the product must fit a launch."""
     with pytest.raises(P.CocodError) as e:
-        dry(W=65535, d=2**34 - 4)
+        dry(W=65535, d=2**34 - 1024)
     assert e.value.status == P.ERR_INVALID and "too large" in str(e.value)
     with pytest.raises(P.CocodError) as e:
         dry(W=2048, d=2**30 + 1024)                       # 2^20 + 1 chunks x 2^11 workers > 2^31 - 1
