@@ -75,19 +75,30 @@ def test_every_step_trains_on_its_own_minibatch():
     g.close()
 
 
-@pytest.mark.parametrize("W,shape,batch,k", [(3, (128, 64, 10), 128, 2), (2, (256, 192, 3), 256, 1), (4, (384, 128, 16), 128, 3)])
+# the last shape has 16 x 2 x 32 = 1024 tiles of 64 x 128 in W1: several per compute unit, 4 M relu decisions per round
+@pytest.mark.parametrize("W,shape,batch,k", [(3, (128, 64, 10), 128, 2), (2, (256, 192, 3), 256, 1), (4, (384, 128, 16), 128, 3),
+                                             (32, (1024, 256, 10), 128, 2)])
 def test_small_networks_rounds(W, shape, batch, k):
     theta0 = synth_inputs.mlp_he_init(11, *shape)
     g = GpuMlp(W, shape, batch, theta0, **HYPER)
     o = mlp.MlpOracle(theta0, W, *shape, batch, **HYPER)
+    # Columns of W1 fed by a hidden unit whose pre-activation came within 2e-5 of zero for some sample are
+    # held to a loose bound only: there the relu decision depends on rounding (the largest shape takes
+    # 4 M such decisions per round and loses one: worker 27, unit 164, in round 2).
     for r in range(4):
         g.ctx.round(k); o.round(k)
-        ex, ev = rel_err(g.x(), o.x), rel_err(g.vel(), o.v)
-        assert ex <= TOL and ev <= TOL, (r, ex, ev)
+        sure = o.certain_mask()
+        gx, gv = g.x(), g.vel()
+        ex, ev = rel_err(gx[sure], o.x[sure]), rel_err(gv[sure], o.v[sure])
+        # once a decision has gone the other way, the next forward pass carries its column's difference into
+        # every gradient: the momentum is then held to ten times the bar, as in the full-size test
+        assert ex <= TOL and ev <= (TOL if sure.all() else 10 * TOL), (r, ex, ev)
+        assert (~sure).mean() < 0.05 and rel_err(gx, o.x) <= 5e-3 and rel_err(gv, o.v) <= 5e-2, (r, (~sure).mean())
     assert g.ctx.get_step() == o.step
     g.ctx.average_begin(); g.ctx.local_steps_end_apply(k)         # same round through the other entry point
     o.round(k)
-    assert rel_err(g.x(), o.x) <= TOL
+    sure = o.certain_mask()
+    assert rel_err(g.x()[sure], o.x[sure]) <= TOL
     g.close()
 
 
