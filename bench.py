@@ -223,6 +223,36 @@ def overlap_figures(ctx, torch, P, s_avg, k, rounds, step_beside_mean_s):
     return out
 
 
+def diagnostics_figures(ctx, torch, stream, W, d, quadratic):
+    """The two scalar diagnostics at this workload: consensus distance sum_i p_i ||x^ - x_i||^2 (read: the W
+    models, 4 B per worker-parameter; timed through the entry point that only enqueues, events around 10
+    calls) and objective + squared gradient norm at the mean (read: models, h, c: 12 B; the call copies
+    its two scalars back, so it is timed by the host clock)."""
+    out = {}
+    result = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    try:
+        ctx.consensus_distance_noalloc(result)
+        ctx.sync()
+        a.record(stream)
+        for _ in range(10):
+            ctx.consensus_distance_noalloc(result)
+        b.record(stream)
+        ctx.sync()
+        ms = a.elapsed_time(b) / 10
+        out["consensus_distance"] = {"ms": ms, "GBps": 4.0 * W * d / ms / 1e6, "value": float(result.item())}
+    except Exception as e:                       # more chunks than the static scratch holds
+        out["consensus_distance"] = {"ms": None, "note": str(e)[:120]}
+    if quadratic:
+        ctx.quadratic_objective()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            f, g2 = ctx.quadratic_objective()
+        ms = (time.perf_counter() - t0) / 5 * 1e3
+        out["quadratic_objective"] = {"ms": ms, "GBps": 12.0 * W * d / ms / 1e6, "f_at_mean": f, "grad_norm_sq_at_mean": g2}
+    return out
+
+
 SINGLE_THREAD_SAMPLE = """
 import json, sys, time
 sys.path.insert(0, %r)
@@ -427,6 +457,7 @@ def bench_quadratic(workload, k, variant, steps, warmup, full):
         ctx.set_schedule(P.SCHED_OVERLAP)
         out["fused_tail_schedule_ms_per_round"] = sched
         out["timelines_ms_per_local_step"] = timelines(ctx, torch, P, k, sweep_rounds)
+        out["diagnostics"] = diagnostics_figures(ctx, torch, wl.s_compute, W, d, True)
         out["external_gradient"] = external_gradient_rounds(ctx, torch, W, d, wl.stride, k, sweep_rounds, wl.h, wl.c)
     wl.close()
     return out

@@ -152,22 +152,33 @@ __global__ __launch_bounds__(kAvgThreads) void mean_correct_kernel(float *x, con
 
 // ---- consensus distance: sum_i p_i || xbar - x_i ||^2 with xbar = sum_i p_i x_i ---------------------
 // (the quantity bounded by Lemma 2 of the paper).  A scalar, so this is where wave and LDS reductions
-// belong: per thread a column quad (two passes over the W rows, the second one from cache), then a
-// butterfly over the wave, the four wave sums through LDS, one double per block; a second one-block
+// belong: per thread a column quad (its W rows held in registers up to 16 workers; above, two passes
+// over the rows, the second one from cache), then a butterfly over the wave, the four wave sums through LDS, one double per block; a second one-block
 // kernel adds the block partials in a fixed order, so the result is deterministic.
-// the same mean with ordinary (cached) loads: the diagnostics read the models twice
+// the same mean with ordinary (cached) loads, for the kernels that read the models a second time
 template <bool WEIGHTED>
 __device__ __forceinline__ float4 column_mean_cached(const float *col, uint64_t stride, uint32_t W, const float *weights)
 {
     MeanSum acc;
     acc.clear();
-    for (uint32_t i = 0; i < W; ++i) {
+    uint32_t i = 0;
+    for (; i + kRowBatch <= W; i += kRowBatch) {
+        float4 r[kRowBatch];
+        #pragma unroll
+        for (int b = 0; b < kRowBatch; ++b) r[b] = ld4(col + static_cast<uint64_t>(i + b) * stride);
+        #pragma unroll
+        for (int b = 0; b < kRowBatch; ++b)
+            acc.add<WEIGHTED>(WEIGHTED ? weights[i + b] : 1.0f, r[b].x, r[b].y, r[b].z, r[b].w);
+    }
+    for (; i < W; ++i) {
         const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
         acc.add<WEIGHTED>(WEIGHTED ? weights[i] : 1.0f, r.x, r.y, r.z, r.w);
     }
     acc.finish<WEIGHTED>(W);
     return make_float4(acc.s[0], acc.s[1], acc.s[2], acc.s[3]);
 }
+
+constexpr uint32_t kRowsInRegisters = 16;   // up to this many workers a thread keeps its whole column quad in registers
 
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
@@ -187,13 +198,41 @@ __global__ __launch_bounds__(kStepThreads) void consensus_partial_kernel(const C
     if (e < ck.n) {
         const float *col = x + static_cast<uint64_t>(ck.mem_quad) * 4 + e;
         const float uniform = 1.0f / static_cast<float>(W);
-        const float4 m = column_mean_cached<WEIGHTED>(col, stride, W, weights);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (uint32_t i = 0; i < W; ++i) {
-            const float4 r = ld4(col + static_cast<uint64_t>(i) * stride);
+        auto add_row = [&](uint32_t i, const float4 &r, const float4 &m) {
             const float pw = WEIGHTED ? weights[i] : uniform;
             acc.x += pw * (r.x - m.x) * (r.x - m.x); acc.y += pw * (r.y - m.y) * (r.y - m.y);
             acc.z += pw * (r.z - m.z) * (r.z - m.z); acc.w += pw * (r.w - m.w) * (r.w - m.w);
+        };
+        if (W <= kRowsInRegisters) {
+            // one pass: every row of the column quad is requested at once and stays in registers for the
+            // squared distances (the guards are uniform over the grid)
+            float4 r[kRowsInRegisters];
+            #pragma unroll
+            for (uint32_t i = 0; i < kRowsInRegisters; ++i)
+                if (i < W) r[i] = ld4_stream(col + static_cast<uint64_t>(i) * stride);
+            MeanSum ms;
+            ms.clear();
+            #pragma unroll
+            for (uint32_t i = 0; i < kRowsInRegisters; ++i)
+                if (i < W) ms.add<WEIGHTED>(WEIGHTED ? weights[i] : 1.0f, r[i].x, r[i].y, r[i].z, r[i].w);
+            ms.finish<WEIGHTED>(W);
+            const float4 m = make_float4(ms.s[0], ms.s[1], ms.s[2], ms.s[3]);
+            #pragma unroll
+            for (uint32_t i = 0; i < kRowsInRegisters; ++i)
+                if (i < W) add_row(i, r[i], m);
+        } else {
+            // two passes over the W rows, the second one from cache
+            const float4 m = column_mean_cached<WEIGHTED>(col, stride, W, weights);
+            uint32_t i = 0;
+            for (; i + kRowBatch <= W; i += kRowBatch) {
+                float4 r[kRowBatch];
+                #pragma unroll
+                for (int b = 0; b < kRowBatch; ++b) r[b] = ld4(col + static_cast<uint64_t>(i + b) * stride);
+                #pragma unroll
+                for (int b = 0; b < kRowBatch; ++b) add_row(i + b, r[b], m);
+            }
+            for (; i < W; ++i) add_row(i, ld4(col + static_cast<uint64_t>(i) * stride), m);
         }
         const uint32_t keep = ck.n - e;                   // alignment pads of a tensor's tail quad do not count
         local = static_cast<double>(acc.x);
@@ -243,15 +282,26 @@ __global__ __launch_bounds__(kStepThreads) void objective_partial_kernel(const C
         const float uniform = 1.0f / static_cast<float>(W);
         const float4 m = column_mean_cached<WEIGHTED>(x + at, stride, W, weights);
         float4 f = make_float4(0.f, 0.f, 0.f, 0.f), g = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (uint32_t i = 0; i < W; ++i) {
-            const float4 hr = ld4(h + at + static_cast<uint64_t>(i) * stride);
-            const float4 cr = ld4(c + at + static_cast<uint64_t>(i) * stride);
+        auto add_row = [&](uint32_t i, const float4 &hr, const float4 &cr) {
             const float pw = WEIGHTED ? weights[i] : uniform;
             const float4 dl = make_float4(m.x - cr.x, m.y - cr.y, m.z - cr.z, m.w - cr.w);
             g.x += pw * hr.x * dl.x; g.y += pw * hr.y * dl.y; g.z += pw * hr.z * dl.z; g.w += pw * hr.w * dl.w;
             f.x += pw * hr.x * dl.x * dl.x; f.y += pw * hr.y * dl.y * dl.y;
             f.z += pw * hr.z * dl.z * dl.z; f.w += pw * hr.w * dl.w * dl.w;
+        };
+        uint32_t i = 0;
+        for (; i + kRowBatch <= W; i += kRowBatch) {              // h and c are read once: streamed, a batch of rows in flight
+            float4 hr[kRowBatch], cr[kRowBatch];
+            #pragma unroll
+            for (int b = 0; b < kRowBatch; ++b) {
+                hr[b] = ld4_stream(h + at + static_cast<uint64_t>(i + b) * stride);
+                cr[b] = ld4_stream(c + at + static_cast<uint64_t>(i + b) * stride);
+            }
+            #pragma unroll
+            for (int b = 0; b < kRowBatch; ++b) add_row(i + b, hr[b], cr[b]);
         }
+        for (; i < W; ++i)
+            add_row(i, ld4_stream(h + at + static_cast<uint64_t>(i) * stride), ld4_stream(c + at + static_cast<uint64_t>(i) * stride));
         const uint32_t keep = ck.n - e;                   // alignment pads of a tensor's tail quad do not count
         f_local = static_cast<double>(f.x);              g_local = static_cast<double>(g.x) * g.x;
         if (keep > 1) { f_local += static_cast<double>(f.y); g_local += static_cast<double>(g.y) * g.y; }
