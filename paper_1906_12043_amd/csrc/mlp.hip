@@ -70,23 +70,23 @@ __device__ __forceinline__ void sgd_update(const MlpParams &p, uint64_t at, floa
 // ---- mini-batch ---------------------------------------------------------------------------------
 // X[b][f] = normal(stream X, worker, step, flat index b*n_in + f);
 // y[b] = (word * n_out) >> 32 from stream Y at index b.
-// One 256-thread block's share of a worker's mini-batch for local step `step`: 256 quads of X, and in
-// block 0 the labels.
-__device__ __forceinline__ void gen_batch_block(const MlpParams &p, uint32_t block, uint32_t worker, uint32_t step,
+// One 256-thread group's share (thread tid of group `block`) of a worker's mini-batch for local step
+// `step`: 256 quads of X, and in group 0 the labels.
+__device__ __forceinline__ void gen_batch_block(const MlpParams &p, uint32_t block, uint32_t tid, uint32_t worker, uint32_t step,
                                                 float *X_all, int32_t *y_all)
 {
     const uint64_t n_quads = static_cast<uint64_t>(p.batch) * p.n_in / 4;
-    const uint64_t q = static_cast<uint64_t>(block) * 256 + threadIdx.x;
+    const uint64_t q = static_cast<uint64_t>(block) * 256 + tid;
     if (q < n_quads) {
         const Normals4 z = box_muller_fast(philox4x32_10(static_cast<uint32_t>(q), step, worker, kTagMlpX, p.key0, p.key1));
         float *X = X_all + static_cast<uint64_t>(worker) * p.batch * p.n_in;
         *reinterpret_cast<f4 *>(X + q * 4) = f4{z.z[0], z.z[1], z.z[2], z.z[3]};
     }
-    if (block == 0 && threadIdx.x < p.batch / 4) {
-        const Words4 r = philox4x32_10(threadIdx.x, step, worker, kTagMlpY, p.key0, p.key1);
+    if (block == 0 && tid < p.batch / 4) {
+        const Words4 r = philox4x32_10(tid, step, worker, kTagMlpY, p.key0, p.key1);
         #pragma unroll
         for (int i = 0; i < 4; ++i)
-            y_all[static_cast<uint64_t>(worker) * p.batch + threadIdx.x * 4 + i] =
+            y_all[static_cast<uint64_t>(worker) * p.batch + tid * 4 + i] =
                 static_cast<int32_t>((static_cast<uint64_t>(r.w[i]) * p.n_out) >> 32);
     }
 }
@@ -99,7 +99,7 @@ __host__ __device__ inline uint32_t gen_batch_blocks(const MlpParams &p)
 __global__ __launch_bounds__(256) void gen_batch_kernel(const MlpParams p)
 {
     const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;
-    gen_batch_block(p, blockIdx.x, blockIdx.y, step, p.X, p.y);
+    gen_batch_block(p, blockIdx.x, threadIdx.x, blockIdx.y, step, p.X, p.y);
 }
 
 // ---- the two big contractions ---------------------------------------------------------------------
@@ -389,20 +389,24 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Output layer, forward and backward, one wave per sample (two samples per wave, eight per block):
+// Output layer, forward and backward, one wave per sample (eight waves and samples per block, so that two
+// waves share a SIMD: a wave's loop is a chain of memory round trips and shuffles):
 //   Z = H W2 + b2 by a strided dot product over the hidden units and a butterfly reduction, softmax
 //   (row maximum subtracted), dZ = (P - onehot(y)) / batch, then dA = (dZ W2^T) * [H > 0] for the
 //   wave's own hidden units.  W2 of the block's worker sits in LDS (row pitch n_out + 1 when n_out
 //   is even, so the 64 lanes of a wave, which read 64 consecutive rows, spread over the banks).
 //   The output width is a template parameter: with it known, the loops over the classes unroll into
 //   straight-line code (as a run-time bound they became a branch per class and per hidden unit).
-constexpr int kHeadSamples = 8;        // per block of 4 waves
+constexpr int kHeadSamples = 8;        // per block: one wave each
 constexpr int kHeadBatch = 8;          // independent loads in flight per lane
+constexpr int kUpdateWaves = 8;                 // head_update: waves per block, each sums an eighth of the batch
+constexpr int kDzGroup = 16, kDzBatch = 16;     //   samples per staged group of dZ rows, and per batch of H / dA loads
 constexpr uint32_t kHeadLdsBytes = 128u << 10;
 __host__ __device__ inline uint32_t head_w2_pitch(uint32_t n_out) { return n_out % 2 == 0 ? n_out + 1 : n_out; }
 template <int NOUT>
-__global__ __launch_bounds__(256) void head_kernel(const MlpParams p)
+__global__ __launch_bounds__(64 * kHeadSamples) void head_kernel(const MlpParams p)
 {
+    constexpr uint32_t THREADS = 64 * kHeadSamples;
     constexpr uint32_t w2_pitch = NOUT % 2 == 0 ? NOUT + 1 : NOUT;
     extern __shared__ float w2s[];     // [n_hid][w2_pitch]
     const uint32_t worker = blockIdx.y;
@@ -412,26 +416,26 @@ __global__ __launch_bounds__(256) void head_kernel(const MlpParams p)
     // W2 -> LDS in 16-byte pieces, four loads in flight per thread (the matrix starts on a 16-byte
     // boundary and holds a multiple of 4 elements, by the shape contract)
     const uint32_t n_quads = p.n_hid * NOUT / 4;
-    for (uint32_t q0 = threadIdx.x; q0 < n_quads; q0 += 256 * 4) {
+    for (uint32_t q0 = threadIdx.x; q0 < n_quads; q0 += THREADS * 4) {
         f4 r[4];
         #pragma unroll
         for (int u = 0; u < 4; ++u)
-            r[u] = q0 + 256 * u < n_quads ? *reinterpret_cast<const f4 *>(theta + o.W2 + 4ull * (q0 + 256 * u)) : f4{0.f, 0.f, 0.f, 0.f};
+            r[u] = q0 + THREADS * u < n_quads ? *reinterpret_cast<const f4 *>(theta + o.W2 + 4ull * (q0 + THREADS * u)) : f4{0.f, 0.f, 0.f, 0.f};
         #pragma unroll
         for (int u = 0; u < 4; ++u)
-            if (q0 + 256 * u < n_quads) {
+            if (q0 + THREADS * u < n_quads) {
                 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t i = 4 * (q0 + 256 * u) + j;
+                    const uint32_t i = 4 * (q0 + THREADS * u) + j;
                     w2s[(i / NOUT) * w2_pitch + i % NOUT] = r[u][j];
                 }
             }
     }
     __syncthreads();
     const float inv_b = 1.0f / static_cast<float>(p.batch);
-    for (uint32_t j = 0; j < kHeadSamples / 4; ++j) {
-        const uint32_t b = blockIdx.x * kHeadSamples + wave * (kHeadSamples / 4) + j;
-        if (b >= p.batch) break;                                   // wave-uniform
+    {
+        const uint32_t b = blockIdx.x * kHeadSamples + wave;
+        if (b >= p.batch) return;                                  // wave-uniform, behind the only barrier
         const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b;
         const float *Hrow = p.H + sample * p.n_hid;
         float z[NOUT];
@@ -486,46 +490,63 @@ __global__ __launch_bounds__(256) void head_kernel(const MlpParams p)
 }
 
 // Gradients of the small parameters and their update.  A block owns 64 hidden units (row n of W2 and
-// b1[n]); its four waves each sum a quarter of the batch and the partial sums meet in LDS in a fixed
+// b1[n]); its eight waves each sum an eighth of the batch and the partial sums meet in LDS in a fixed
 // order.  Block 0 of a worker also owns b2 and the alignment pads.
 template <int NOUT>
-__global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
+__global__ __launch_bounds__(64 * kUpdateWaves) void head_update_kernel(const MlpParams p)
 {
-    __shared__ float part[4][64][NOUT + 1];
-    const uint32_t worker = blockIdx.y;
-    // The blocks behind the (n_hid + 63) / 64 that own hidden units draw the NEXT local step's mini-batch
-    // into the other batch buffer: this kernel is a short chain of dependent loads on one block per
-    // compute unit, and the generator is pure vector arithmetic that fills the rest of the chip meanwhile.
+    __shared__ float part[kUpdateWaves][64][NOUT + 1];
+    __shared__ __attribute__((aligned(16))) float dzs[kUpdateWaves][kDzGroup][kMaxOut];     // per wave: dZ rows of the current group
+    // The first W * ceil(n_hid / 64) blocks own hidden units.  The blocks behind them draw the NEXT local
+    // step's mini-batch into the other batch buffer: the owners are a short chain of dependent loads on one
+    // block per compute unit, and the generator is pure vector arithmetic that fills the rest of the chip
+    // meanwhile.  Blocks are dispatched in the order of their index: the owners, whose chain decides when
+    // the kernel ends, all start at once.
     const uint32_t own_blocks = (p.n_hid + 63) / 64;
-    if (blockIdx.x >= own_blocks) {
+    if (blockIdx.x >= own_blocks * p.W) {
+        constexpr uint32_t GROUPS = kUpdateWaves / 4;                // 256-thread generator groups per block
+        const uint32_t id = blockIdx.x - own_blocks * p.W, per_worker = (gen_batch_blocks(p) + GROUPS - 1) / GROUPS;
         const uint32_t step = p.step_base ? *p.step_base + p.step : p.step;
-        gen_batch_block(p, blockIdx.x - own_blocks, worker, step + 1, p.X_next, p.y_next);
+        gen_batch_block(p, (id % per_worker) * GROUPS + threadIdx.x / 256, threadIdx.x % 256, id / per_worker, step + 1, p.X_next, p.y_next);
         return;
     }
+    const uint32_t worker = blockIdx.x / own_blocks, own = blockIdx.x % own_blocks;
     const uint32_t u = threadIdx.x % 64, slice = threadIdx.x / 64;
-    const uint32_t n = blockIdx.x * 64 + u;
+    const uint32_t n = own * 64 + u;
     const Offsets o = offsets_of(p);
     const uint64_t base = static_cast<uint64_t>(worker) * p.stride;
     float gw[NOUT];
     #pragma unroll
     for (int c = 0; c < NOUT; ++c) gw[c] = 0.0f;
     float gb = 0.0f;
-    if (n < p.n_hid) {
-        const uint32_t per = p.batch / 4;                            // a multiple of 32 by the shape contract
-        for (uint32_t b0 = slice * per; b0 < (slice + 1) * per; b0 += kHeadBatch) {
-            float hv[kHeadBatch], da[kHeadBatch];                    // the batch's loads are all in flight together
+    {
+        // The wave's eighth of the batch in groups of 16 samples.  Every lane needs the same dZ rows: the wave
+        // fetches a group's rows once (one quad per lane) into its own piece of LDS and reads them back as
+        // broadcasts, instead of 10 same-address loads per sample and lane.
+        const uint32_t per = p.batch / kUpdateWaves;                 // a multiple of 16 by the shape contract
+        const bool mine = n < p.n_hid;
+        for (uint32_t g0 = slice * per; g0 < (slice + 1) * per; g0 += kDzGroup) {
+            const float *dz_rows = p.dZ + (static_cast<uint64_t>(worker) * p.batch + g0) * kMaxOut;
+            static_assert(kDzGroup * kMaxOut == 4 * 64, "one quad of the group's dZ rows per lane");
+            const f4 q0 = *reinterpret_cast<const f4 *>(dz_rows + 4 * u);
             #pragma unroll
-            for (int j = 0; j < kHeadBatch; ++j) {
-                const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b0 + j;
-                hv[j] = p.H[sample * p.n_hid + n];
-                da[j] = p.dA[sample * p.n_hid + n];
-            }
-            #pragma unroll
-            for (int j = 0; j < kHeadBatch; ++j) {
-                gb += da[j];
-                const float *dz = p.dZ + (static_cast<uint64_t>(worker) * p.batch + b0 + j) * kMaxOut;
+            for (int half = 0; half < kDzGroup / kDzBatch; ++half) {
+                float hv[kDzBatch], da[kDzBatch];                    // the batch's loads are all in flight together
                 #pragma unroll
-                for (int c = 0; c < NOUT; ++c) gw[c] += hv[j] * dz[c];
+                for (int j = 0; j < kDzBatch; ++j) {
+                    const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + g0 + half * kDzBatch + j;
+                    hv[j] = mine ? p.H[sample * p.n_hid + n] : 0.0f;
+                    da[j] = mine ? p.dA[sample * p.n_hid + n] : 0.0f;
+                }
+                if (half == 0) {                                     // rows of the group -> LDS (this wave's piece only)
+                    *reinterpret_cast<f4 *>(&dzs[slice][0][0] + 4 * u) = q0;
+                }
+                #pragma unroll
+                for (int j = 0; j < kDzBatch; ++j) {
+                    gb += da[j];
+                    #pragma unroll
+                    for (int c = 0; c < NOUT; ++c) gw[c] += hv[j] * dzs[slice][half * kDzBatch + j][c];
+                }
             }
         }
     }
@@ -546,7 +567,9 @@ __global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
         #pragma unroll
         for (int c = 0; c <= NOUT; ++c) {
             {
-                const float G = ((part[0][u][c] + part[1][u][c]) + part[2][u][c]) + part[3][u][c];
+                float G = part[0][u][c];
+                #pragma unroll
+                for (int w = 1; w < kUpdateWaves; ++w) G += part[w][u][c];
                 float g = G + p.weight_decay * xo[c];
                 if (p.momentum != 0.0f) {
                     g = p.momentum * vo[c] + g;
@@ -558,7 +581,7 @@ __global__ __launch_bounds__(256) void head_update_kernel(const MlpParams p)
             }
         }
     }
-    if (blockIdx.x == 0 && slice == 1) {
+    if (own == 0 && slice == 1) {
         // db2[c] = sum_b dZ[b][c]: lanes take the samples 64 apart, then a butterfly over the wave
         float col[NOUT];
         #pragma unroll
@@ -586,10 +609,12 @@ hipError_t launch_heads_for(hipStream_t stream, const MlpParams &p)
     static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(head_kernel<NOUT>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kHeadLdsBytes);
     if (lds_ok != hipSuccess) return lds_ok;
-    hipLaunchKernelGGL(head_kernel<NOUT>, dim3((p.batch + kHeadSamples - 1) / kHeadSamples, p.W), dim3(256),
+    hipLaunchKernelGGL(head_kernel<NOUT>, dim3((p.batch + kHeadSamples - 1) / kHeadSamples, p.W), dim3(64 * kHeadSamples),
                        static_cast<size_t>(p.n_hid) * head_w2_pitch(NOUT) * sizeof(float), stream, p);
-    hipLaunchKernelGGL(head_update_kernel<NOUT>, dim3((p.n_hid + 63) / 64 + (p.X_next ? gen_batch_blocks(p) : 0u), p.W),
-                       dim3(256), 0, stream, p);
+    const uint32_t gen_blocks = p.X_next ? (gen_batch_blocks(p) + kUpdateWaves / 4 - 1) / (kUpdateWaves / 4) : 0u;
+    const uint64_t update_blocks = (static_cast<uint64_t>((p.n_hid + 63) / 64) + gen_blocks) * p.W;
+    if (update_blocks > 0x7fffffffull) return hipErrorInvalidValue;      // a mini-batch of terabytes: its work space was never allocated
+    hipLaunchKernelGGL(head_update_kernel<NOUT>, dim3(static_cast<uint32_t>(update_blocks)), dim3(64 * kUpdateWaves), 0, stream, p);
     return hipSuccess;
 }
 
