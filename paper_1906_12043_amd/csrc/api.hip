@@ -32,6 +32,7 @@ struct cocod_ctx {
     // its output layer runs, so that only the first step after anything else draws its own up front.
     float *mlp_X[2] = {nullptr, nullptr};
     int32_t *mlp_y[2] = {nullptr, nullptr};
+    uint32_t compute_units = 0;         // of the device the context was created on
     uint32_t batch_buf = 0;             // buffer the next eager step takes its batch from
     uint32_t batch_last = 0;            // buffer the most recent step took its batch from
     uint64_t batch_ready_step = ~0ull;  // mlp_X[batch_buf] holds the batch of this step index (~0: of none)
@@ -270,9 +271,16 @@ void release(cocod_ctx *ctx)
 // Step I arithmetic on `stream`, one launch per bucket.
 int enqueue_mean(cocod_ctx *ctx, hipStream_t stream)
 {
+    // Perceptron workers, mean on the averaging stream: the kernel beside it is the forward contraction, which
+    // needs a steady trickle of its weight stream and little bandwidth.  At full width the mean takes the memory
+    // system for its 43 us and the contraction loses 36 of them; in four single-wave blocks per compute unit it
+    // takes longer and the round is 15 us shorter (W = 16, 3072-1024-10, k = 2: 0.705 -> 0.690 ms; two blocks per
+    // unit: 0.700, one or eight: 0.709; k = 1, where the step waits for the mean: unchanged, 0.392 ms).
+    const uint32_t cap = ctx->cfg.grad == COCOD_GRAD_MLP && stream == ctx->s_avg && ctx->s_avg != ctx->s_compute
+                             ? 4u * ctx->compute_units : 0u;
     for (size_t b = 0; b + 1 < ctx->bucket_begin.size(); ++b)
         COCOD_HIP(ctx, cocod::launch_wmean(stream, ctx->snap, ctx->cfg.stride, ctx->cfg.W, ctx->bucket_begin[b],
-                                           ctx->bucket_begin[b + 1], ctx->d_weights, ctx->cfg.mean));
+                                           ctx->bucket_begin[b + 1], ctx->d_weights, ctx->cfg.mean, cap));
     return COCOD_OK;
 }
 
@@ -395,6 +403,12 @@ int cocod_create(const cocod_config *cfg, cocod_ctx **out)
                 ctx->mlp.X = ctx->mlp_X[0];
                 ctx->mlp.y = ctx->mlp_y[0];
             }
+        }
+        if (e == hipSuccess) {
+            int dev = 0, cus = 0;
+            e = hipGetDevice(&dev);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+            ctx->compute_units = cus > 0 ? static_cast<uint32_t>(cus) : 0u;
         }
         if (e == hipSuccess) e = scratch_for_current_device(&ctx->static_scratch);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_snap, hipEventDisableTiming);

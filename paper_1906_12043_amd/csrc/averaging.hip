@@ -70,10 +70,11 @@ __global__ __launch_bounds__(kAvgThreads) void wmean_kernel(const float *snap, u
     // Line 6 waits for this kernel while the local step beside it has no one waiting: its waves issue first
     // (0.20 -> 0.18 ms next to the step; the round's time does not change).
     __builtin_amdgcn_s_setprio(3);
-    const uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x;
-    if (quad >= n_quads) return;
-    const uint64_t e = begin + quad * 4;
-    st4(mean + e, column_mean<WEIGHTED>(snap + e, stride, W, weights));
+    for (uint64_t quad = static_cast<uint64_t>(blockIdx.x) * kAvgThreads + threadIdx.x; quad < n_quads;
+         quad += static_cast<uint64_t>(gridDim.x) * kAvgThreads) {
+        const uint64_t e = begin + quad * 4;
+        st4(mean + e, column_mean<WEIGHTED>(snap + e, stride, W, weights));
+    }
 }
 
 __device__ __forceinline__ void correct_column(float *xcol, const float *scol, const float4 m, uint64_t stride, uint32_t W)
@@ -325,11 +326,13 @@ inline uint32_t blocks_for(uint64_t n_quads) { return static_cast<uint32_t>((n_q
 }  // namespace
 
 hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, uint32_t W, uint64_t begin,
-                        uint64_t end, const float *weights, float *mean)
+                        uint64_t end, const float *weights, float *mean, uint32_t max_blocks)
 {
     const uint64_t n_quads = (end - begin) / 4;
     if (n_quads == 0) return hipSuccess;
-    const dim3 grid(blocks_for(n_quads)), block(kAvgThreads);
+    uint32_t blocks = blocks_for(n_quads);
+    if (max_blocks != 0 && max_blocks < blocks) blocks = max_blocks;     // the kernel strides over the rest
+    const dim3 grid(blocks), block(kAvgThreads);
     if (weights) hipLaunchKernelGGL((wmean_kernel<true>), grid, block, 0, stream, snap, stride, W, begin, n_quads, weights, mean);
     else         hipLaunchKernelGGL((wmean_kernel<false>), grid, block, 0, stream, snap, stride, W, begin, n_quads, weights, mean);
     return hipGetLastError();

@@ -61,9 +61,10 @@ hipError_t launch_line6(hipStream_t stream, const StepParams &p);
 int local_step_mean_quads_per_lane(uint32_t W, bool one_pass);
 
 // mean[e] = sum_i p_i snap[i][e] for e in [begin, end) (both multiples of 4);
-// weights == nullptr means p_i = 1/W.
+// weights == nullptr means p_i = 1/W.  max_blocks != 0 caps the grid (single-wave blocks that stride over
+// the columns): a mean that runs beside a kernel it should not starve.
 hipError_t launch_wmean(hipStream_t stream, const float *snap, uint64_t stride, uint32_t W,
-                        uint64_t begin, uint64_t end, const float *weights, float *mean);
+                        uint64_t begin, uint64_t end, const float *weights, float *mean, uint32_t max_blocks);
 
 // the mean and line 6, x[i][e] = mean[e] + (x[i][e] - snap[i][e]), in one pass; mean is still written
 hipError_t launch_mean_correct(hipStream_t stream, float *x, const float *snap, uint64_t stride,
