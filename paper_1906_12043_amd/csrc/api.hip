@@ -497,13 +497,12 @@ static int enqueue_step(cocod_ctx *ctx, bool with_line6, const void *g_ext = nul
         p.snap = with_line6 ? ctx->snap : nullptr;
         p.mean = ctx->cfg.mean;
         const bool timed = ctx->timing && ctx->t_used < ctx->t_start.size();
-        if (timed) COCOD_HIP(ctx, hipEventRecord(ctx->t_start[ctx->t_used], ctx->s_compute));
-        COCOD_HIP(ctx, cocod::launch_mlp_step(ctx->s_compute, p));
+        COCOD_HIP(ctx, cocod::launch_mlp_step(ctx->s_compute, p, timed ? ctx->t_start[ctx->t_used] : nullptr,
+                                              timed ? ctx->t_stop[ctx->t_used] : nullptr));
         ctx->batch_last = buf;
         ctx->batch_buf = buf ^ 1u;
         ctx->batch_ready_step = ctx->step + 1;
         if (timed) {
-            COCOD_HIP(ctx, hipEventRecord(ctx->t_stop[ctx->t_used], ctx->s_compute));
             ctx->t_kind[ctx->t_used] = with_line6 ? 1 : 0;
             ctx->t_used += 1;
         }

@@ -110,7 +110,8 @@ struct MlpParams {
 
 bool mlp_shape_supported(uint32_t n_in, uint32_t n_hid, uint32_t n_out, uint32_t batch);
 size_t mlp_dz_pitch();
-hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p);
+// start / stop (may be null) receive the start timestamp of the step's first kernel and the end timestamp of its last
+hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p, hipEvent_t start, hipEvent_t stop);
 
 hipError_t launch_copy(hipStream_t stream, const float *src, float *dst, uint64_t n_quads);
 

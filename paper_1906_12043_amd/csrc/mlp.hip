@@ -27,6 +27,8 @@
 #include "internal.hpp"
 #include "philox.hpp"
 
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 #include <utility>
 
@@ -375,10 +377,13 @@ __global__ __launch_bounds__(64 * NWM * NWN) void mlp_gemm_kernel(const MlpParam
 }
 
 template <int EPI, int NWM, int NWN>
-void launch_gemm(hipStream_t stream, const MlpParams &p)
+void launch_gemm(hipStream_t stream, const MlpParams &p, hipEvent_t start = nullptr, hipEvent_t stop = nullptr)
 {
     const uint32_t M = (EPI == kFwd) ? p.batch : p.n_in;
-    hipLaunchKernelGGL((mlp_gemm_kernel<EPI, NWM, NWN>), dim3(p.n_hid / (32 * NWN), M / (32 * NWM), p.W), dim3(64 * NWM * NWN), 0, stream, p);
+    const dim3 grid(p.n_hid / (32 * NWN), M / (32 * NWM), p.W), block(64 * NWM * NWN);
+    // the events, if any, take the kernel's own start / end timestamps (no marker of their own in the queue)
+    if (start || stop) hipExtLaunchKernelGGL((mlp_gemm_kernel<EPI, NWM, NWN>), grid, block, 0, stream, start, stop, 0, p);
+    else               hipLaunchKernelGGL((mlp_gemm_kernel<EPI, NWM, NWN>), grid, block, 0, stream, p);
 }
 
 // ---- output layer -----------------------------------------------------------------------------------
@@ -638,15 +643,19 @@ bool mlp_shape_supported(uint32_t n_in, uint32_t n_hid, uint32_t n_out, uint32_t
 
 size_t mlp_dz_pitch() { return kMaxOut; }
 
-hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p)
+hipError_t launch_mlp_step(hipStream_t stream, const MlpParams &p, hipEvent_t start, hipEvent_t stop)
 {
     const bool wide = p.n_hid % 128 == 0;      // 64 x 128 block tiles (fastest measured), else 64 x 64
-    if (!p.have_batch) hipLaunchKernelGGL(gen_batch_kernel, dim3(gen_batch_blocks(p), p.W), dim3(256), 0, stream, p);
-    if (wide) launch_gemm<kFwd, 2, 4>(stream, p); else launch_gemm<kFwd, 2, 2>(stream, p);
+    if (!p.have_batch) {                       // the step then begins with this kernel
+        if (start) hipExtLaunchKernelGGL(gen_batch_kernel, dim3(gen_batch_blocks(p), p.W), dim3(256), 0, stream, start, nullptr, 0, p);
+        else       hipLaunchKernelGGL(gen_batch_kernel, dim3(gen_batch_blocks(p), p.W), dim3(256), 0, stream, p);
+        start = nullptr;
+    }
+    if (wide) launch_gemm<kFwd, 2, 4>(stream, p, start); else launch_gemm<kFwd, 2, 2>(stream, p, start);
     const hipError_t head_rc = launch_heads(stream, p, std::make_integer_sequence<int, kMaxOut>{});
     if (head_rc != hipSuccess) return head_rc;
-    if (p.snap) { if (wide) launch_gemm<kBwdTail, 2, 4>(stream, p); else launch_gemm<kBwdTail, 2, 2>(stream, p); }
-    else        { if (wide) launch_gemm<kBwd, 2, 4>(stream, p); else launch_gemm<kBwd, 2, 2>(stream, p); }
+    if (p.snap) { if (wide) launch_gemm<kBwdTail, 2, 4>(stream, p, nullptr, stop); else launch_gemm<kBwdTail, 2, 2>(stream, p, nullptr, stop); }
+    else        { if (wide) launch_gemm<kBwd, 2, 4>(stream, p, nullptr, stop); else launch_gemm<kBwd, 2, 2>(stream, p, nullptr, stop); }
     return hipGetLastError();
 }
 
