@@ -279,6 +279,8 @@ int cocod_get_plan(const cocod_ctx *ctx, uint64_t *padded_d, uint32_t *n_chunks,
  * launches carry the runtime's own start/stop timestamps (events on compute_stream, owned by the
  * context); n = 0 switches it off.  cocod_step_timing_read waits for compute_stream, returns the
  * summed kernel durations and the number of launches measured since the last read, and rearms.
+ * A local step of the MLP kind is several kernels: its duration runs from the start of the first
+ * to the end of the last.
  * Index 0 of both arrays: plain local steps; index 1: steps that carry line 6
  * (cocod_local_steps_end_apply's last step, the one-pass k = 1 step included); index 2: first steps
  * of a round that also form the mean (COCOD_SCHED_HEAD).
