@@ -84,7 +84,7 @@ def test_small_networks_rounds(W, shape, batch, k):
     o = mlp.MlpOracle(theta0, W, *shape, batch, **HYPER)
     # Columns of W1 fed by a hidden unit whose pre-activation came within 2e-5 of zero for some sample are
     # held to a loose bound only: there the relu decision depends on rounding (the largest shape takes
-    # 4 M such decisions per round and loses one: worker 27, unit 164, in round 2).
+    # 4 M such decisions per round and loses one: worker 27, unit 164, in the second averaging round).
     for r in range(4):
         g.ctx.round(k); o.round(k)
         sure = o.certain_mask()
