@@ -404,6 +404,7 @@ __device__ __forceinline__ float wave_sum(float v)
 //   straight-line code (as a run-time bound they became a branch per class and per hidden unit).
 constexpr int kHeadSamples = 8;        // per block: one wave each
 constexpr int kHeadBatch = 8;          // independent loads in flight per lane
+constexpr int kHeadKeep = 2;           // head: batches of a sample's H row that stay in registers (1024 hidden units)
 constexpr int kUpdateWaves = 8;                 // head_update: waves per block, each sums an eighth of the batch
 constexpr int kDzGroup = 16, kDzBatch = 16;     //   samples per staged group of dZ rows, and per batch of H / dA loads
 constexpr uint32_t kHeadLdsBytes = 128u << 10;
@@ -418,6 +419,21 @@ __global__ __launch_bounds__(64 * kHeadSamples) void head_kernel(const MlpParams
     const uint32_t lane = threadIdx.x % 64, wave = threadIdx.x / 64;
     const Offsets o = offsets_of(p);
     const float *theta = p.x_in + static_cast<uint64_t>(worker) * p.stride;
+    // The wave's sample, and the first kHeadKeep batches of its H row: requested before anything else (they
+    // arrive while W2 is staged) and kept in registers for the second pass.
+    const uint32_t b = blockIdx.x * kHeadSamples + wave;
+    const bool have_sample = b < p.batch;                              // wave-uniform
+    const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + (have_sample ? b : 0u);
+    const float *Hrow = p.H + sample * p.n_hid;
+    float hkeep[kHeadKeep][kHeadBatch];
+    #pragma unroll
+    for (int it = 0; it < kHeadKeep; ++it) {
+        #pragma unroll
+        for (int u = 0; u < kHeadBatch; ++u) {
+            const uint32_t n = lane + 64u * (u + kHeadBatch * it);
+            hkeep[it][u] = n < p.n_hid ? Hrow[n] : 0.0f;
+        }
+    }
     // W2 -> LDS in 16-byte pieces, four loads in flight per thread (the matrix starts on a 16-byte
     // boundary and holds a multiple of 4 elements, by the shape contract)
     const uint32_t n_quads = p.n_hid * NOUT / 4;
@@ -439,16 +455,25 @@ __global__ __launch_bounds__(64 * kHeadSamples) void head_kernel(const MlpParams
     __syncthreads();
     const float inv_b = 1.0f / static_cast<float>(p.batch);
     {
-        const uint32_t b = blockIdx.x * kHeadSamples + wave;
-        if (b >= p.batch) return;                                  // wave-uniform, behind the only barrier
-        const uint64_t sample = static_cast<uint64_t>(worker) * p.batch + b;
-        const float *Hrow = p.H + sample * p.n_hid;
+        if (!have_sample) return;                                  // behind the only barrier
         float z[NOUT];
         #pragma unroll
         for (int c = 0; c < NOUT; ++c) z[c] = 0.0f;
-        // the wave's hidden units in batches of kHeadBatch loads in flight (one load at a time would
-        // make the loop a chain of memory latencies)
-        for (uint32_t n0 = lane; n0 < p.n_hid; n0 += 64 * kHeadBatch) {
+        #pragma unroll
+        for (int it = 0; it < kHeadKeep; ++it) {
+            #pragma unroll
+            for (int u = 0; u < kHeadBatch; ++u) {
+                const uint32_t n = lane + 64u * (u + kHeadBatch * it);
+                if (n < p.n_hid) {
+                    const float *w2 = w2s + n * w2_pitch;
+                    #pragma unroll
+                    for (int c = 0; c < NOUT; ++c) z[c] += hkeep[it][u] * w2[c];
+                }
+            }
+        }
+        // hidden units beyond the kept ones in batches of kHeadBatch loads in flight (one load at a time
+        // would make the loop a chain of memory latencies)
+        for (uint32_t n0 = lane + 64u * kHeadBatch * kHeadKeep; n0 < p.n_hid; n0 += 64 * kHeadBatch) {
             float hv[kHeadBatch];
             #pragma unroll
             for (int u = 0; u < kHeadBatch; ++u) hv[u] = n0 + 64 * u < p.n_hid ? Hrow[n0 + 64 * u] : 0.0f;
@@ -476,7 +501,21 @@ __global__ __launch_bounds__(64 * kHeadSamples) void head_kernel(const MlpParams
             z[c] = (z[c] / denom - (label == c ? 1.0f : 0.0f)) * inv_b;                // dZ, the same in every lane
             if (lane == static_cast<uint32_t>(c)) p.dZ[sample * kMaxOut + c] = z[c];
         }
-        for (uint32_t n0 = lane; n0 < p.n_hid; n0 += 64 * kHeadBatch) {
+        #pragma unroll
+        for (int it = 0; it < kHeadKeep; ++it) {
+            #pragma unroll
+            for (int u = 0; u < kHeadBatch; ++u) {
+                const uint32_t n = lane + 64u * (u + kHeadBatch * it);
+                if (n < p.n_hid) {
+                    const float *w2 = w2s + n * w2_pitch;
+                    float dh = 0.0f;
+                    #pragma unroll
+                    for (int c = 0; c < NOUT; ++c) dh += z[c] * w2[c];
+                    p.dA[sample * p.n_hid + n] = hkeep[it][u] > 0.0f ? dh : 0.0f;
+                }
+            }
+        }
+        for (uint32_t n0 = lane + 64u * kHeadBatch * kHeadKeep; n0 < p.n_hid; n0 += 64 * kHeadBatch) {
             float hv[kHeadBatch];
             #pragma unroll
             for (int u = 0; u < kHeadBatch; ++u) hv[u] = n0 + 64 * u < p.n_hid ? Hrow[n0 + 64 * u] : 0.0f;

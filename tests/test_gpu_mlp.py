@@ -17,7 +17,9 @@ TOL = 1e-4
 HYPER = dict(lr=0.05, momentum=0.9, weight_decay=1e-3, seed=0x5EED0004)
 
 
-@pytest.mark.parametrize("W,shape,batch", [(2, (128, 64, 10), 128), (3, (256, 192, 3), 256), (1, (384, 128, 16), 128)])
+# the last shape has more hidden units (1152) than the output-layer kernel keeps of a sample's row in registers (1024)
+@pytest.mark.parametrize("W,shape,batch", [(2, (128, 64, 10), 128), (3, (256, 192, 3), 256), (1, (384, 128, 16), 128),
+                                           (2, (128, 1152, 10), 128)])
 def test_pieces_of_one_step(W, shape, batch):
     n_in, n_hidden, n_out = shape
     theta0 = synth_inputs.mlp_he_init(7, *shape).astype(np.float64)
