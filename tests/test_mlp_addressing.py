@@ -115,3 +115,45 @@ def test_backward_product_and_its_update_stay_inside_their_operands(n_in, n_hid,
 def test_slice_schedules_cover_every_slice_and_never_run_past_the_last(n_slices):
     assert forward_slices_loaded(n_slices) == list(range(n_slices))
     assert backward_slices_loaded(n_slices) == list(range(n_slices))
+
+
+# ---- output-layer kernels --------------------------------------------------------------------------
+
+HEAD_BATCH, HEAD_KEEP, HEAD_SAMPLES = 8, 2, 8          # loads in flight per lane, kept batches, samples (= waves) per block
+UPDATE_WAVES, DZ_GROUP, DZ_PITCH = 8, 16, 16           # waves per block, samples per staged group of dZ rows, row pitch of dZ
+
+
+@pytest.mark.parametrize("n_hid", [64, 192, 1024, 1152, 2944])
+@pytest.mark.parametrize("batch", [128, 384, 1024])
+def test_output_layer_kernels_stay_inside_their_arrays(n_hid, batch):
+    """head: a wave's sample and the hidden units it touches (the kept part of the row first, then batches of
+    eight); head_update: a wave's eighth of the batch in groups of 16 samples, one quad of the group's dZ rows
+    per lane; the generator groups appended to that launch.  Last worker, tightest buffers."""
+    W, n_in = 3, 128
+    lanes = np.arange(64, dtype=np.int64)
+    # head: blocks of HEAD_SAMPLES waves, one sample each; H is [W][batch][n_hid]
+    blocks = (batch + HEAD_SAMPLES - 1) // HEAD_SAMPLES
+    samples = np.arange(blocks * HEAD_SAMPLES)
+    assert samples[samples < batch].max() == batch - 1                   # waves past the batch take no sample (they load sample 0's row)
+    kept = lanes[None, :] + 64 * np.arange(HEAD_BATCH * HEAD_KEEP)[:, None]
+    beyond = np.arange(64 * HEAD_BATCH * HEAD_KEEP, max(n_hid, 64 * HEAD_BATCH * HEAD_KEEP) + 64 * HEAD_BATCH)
+    touched = np.concatenate([kept.ravel(), beyond])
+    touched = touched[touched < n_hid]                                   # every access is guarded by n < n_hid
+    assert sorted(set(touched.tolist())) == list(range(n_hid))           # each hidden unit exactly once per sample
+    assert (W - 1) * batch * n_hid + (batch - 1) * n_hid + touched.max() < W * batch * n_hid
+    # head_update: per wave batch / 8 samples in groups of DZ_GROUP; lane u loads quad u of the group's rows
+    per = batch // UPDATE_WAVES
+    assert per % DZ_GROUP == 0 and DZ_GROUP * DZ_PITCH == 4 * 64
+    first_rows = np.array([s * per + g for s in range(UPDATE_WAVES) for g in range(0, per, DZ_GROUP)])
+    dz_elem = ((W - 1) * batch + first_rows[:, None]) * DZ_PITCH + 4 * lanes[None, :] + 3
+    assert dz_elem.max() < W * batch * DZ_PITCH and first_rows.max() + DZ_GROUP == batch
+    covered = sorted(set((first_rows[:, None] + np.arange(DZ_GROUP)[None, :]).ravel().tolist()))
+    assert covered == list(range(batch))                                 # every sample summed exactly once
+    # generator groups of 256 threads, UPDATE_WAVES / 4 per block: quads of X [batch][n_in] per worker
+    n_quads = batch * n_in // 4
+    groups = (n_quads + 255) // 256
+    per_block = UPDATE_WAVES // 4
+    blocks_per_worker = (groups + per_block - 1) // per_block
+    q = (np.arange(blocks_per_worker * per_block)[:, None] * 256 + np.arange(256)[None, :]).ravel()
+    q = q[q < n_quads]                                                   # the kernel's own guard
+    assert sorted(q.tolist()) == list(range(n_quads))                    # every quad drawn exactly once
